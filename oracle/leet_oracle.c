@@ -1,0 +1,162 @@
+/*
+ * fp64 CPU oracle for exponentially decaying causal linear attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may call this file;
+ * it exists so that the HIP kernels can be checked against a slow, plain,
+ * obviously correct statement of what the paper's operator computes.  It
+ * shares no code, header, table or helper with the HIP library.
+ *
+ * Operator (Section 2.2, Eq. "BCMV" with B = Q, C = K):
+ *     O = ((Q K^T) .* M) V,   M[i][j] = gamma^(i-j) if i >= j else 0.
+ * No softmax, no row normalisation, no 1/sqrt(d) (Section 2.1 drops it).
+ * gamma is one value per head; gamma = 1 is plain causal linear attention.
+ * 0^0 is taken as 1, so the diagonal weight is always 1.
+ *
+ * Two independent forms are given:
+ *   form 1  leet_oracle_quadratic*  the definition written out (the paper's
+ *           "vanilla" method), O(N^2 d);
+ *   form 2  leet_oracle_recurrent / leet_oracle_decode_step  the row-based
+ *           algorithm (Appendix B.1, Alg. 1) with the discount of the
+ *           lambda-cumsum recurrence O_i = V_i + lambda O_{i-1}
+ *           (Appendix C.1):   U <- gamma U + k_i^T v_i ;  o_i = q_i U.
+ *           The state is updated before the output is taken, so token i
+ *           sees itself with weight gamma^0 = 1, as M[i][i] = 1 demands.
+ *
+ * Layout everywhere: q, k, v, out are [B][H][N][d] row-major doubles; gamma
+ * is [H]; a state is [B][H][d][d] with rows = key index, cols = value index.
+ * All parity pins live in tests/ (not here).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* gamma^n for integer n >= 0, by the library pow, with 0^0 = 1. */
+static double decay_weight(double gamma, long n)
+{
+    if (n == 0) return 1.0;
+    return pow(gamma, (double)n);
+}
+
+/* Form 1 for one output row i of one (b,h): o_i = sum_{j<=i} gamma^(i-j) (q_i.k_j) v_j. */
+static void quadratic_row(const double *q, const double *k, const double *v,
+                          double gamma, long i, int d, double *o)
+{
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    for (long j = 0; j <= i; ++j) {
+        double a = 0.0;
+        for (int e = 0; e < d; ++e) a += q[i * d + e] * k[j * d + e];
+        a *= decay_weight(gamma, i - j);
+        for (int c = 0; c < d; ++c) o[c] += a * v[j * d + c];
+    }
+}
+
+/* Form 1, whole tensors. */
+int leet_oracle_quadratic(const double *q, const double *k, const double *v,
+                          const double *gamma, double *out,
+                          int B, int H, long N, int d)
+{
+    if (!q || !k || !v || !gamma || !out || B <= 0 || H <= 0 || N <= 0 || d <= 0) return 1;
+    long BH = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (long bh = 0; bh < BH; ++bh) {
+        for (long i = 0; i < N; ++i) {
+            size_t base = (size_t)bh * N * d;
+            quadratic_row(q + base, k + base, v + base, gamma[bh % H], i, d,
+                          out + base + (size_t)i * d);
+        }
+    }
+    return 0;
+}
+
+/* Form 1 on selected rows only: rows[r] = {b*H+h, i}; out_rows is [nrows][d]. */
+int leet_oracle_quadratic_rows(const double *q, const double *k, const double *v,
+                               const double *gamma, const long *rows, long nrows,
+                               double *out_rows, int B, int H, long N, int d)
+{
+    if (!q || !k || !v || !gamma || !rows || !out_rows || B <= 0 || H <= 0 || N <= 0 || d <= 0) return 1;
+    for (long r = 0; r < nrows; ++r) {
+        long bh = rows[2 * r], i = rows[2 * r + 1];
+        if (bh < 0 || bh >= (long)B * H || i < 0 || i >= N) return 1;
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < nrows; ++r) {
+        long bh = rows[2 * r], i = rows[2 * r + 1];
+        size_t base = (size_t)bh * N * d;
+        quadratic_row(q + base, k + base, v + base, gamma[bh % H], i, d,
+                      out_rows + (size_t)r * d);
+    }
+    return 0;
+}
+
+/* One token of form 2 on one (b,h) state U[d][d]. */
+static void recurrent_token(double *U, const double *qi, const double *ki,
+                            const double *vi, double gamma, int d, double *oi)
+{
+    for (int e = 0; e < d; ++e)
+        for (int c = 0; c < d; ++c)
+            U[(size_t)e * d + c] = gamma * U[(size_t)e * d + c] + ki[e] * vi[c];
+    for (int c = 0; c < d; ++c) oi[c] = 0.0;
+    for (int e = 0; e < d; ++e)
+        for (int c = 0; c < d; ++c)
+            oi[c] += qi[e] * U[(size_t)e * d + c];
+}
+
+/*
+ * Form 2, whole tensors.  state_in may be NULL (zero state); state_out may be
+ * NULL.  state_out receives the state after the last token.
+ */
+int leet_oracle_recurrent(const double *q, const double *k, const double *v,
+                          const double *gamma, const double *state_in,
+                          double *out, double *state_out,
+                          int B, int H, long N, int d)
+{
+    if (!q || !k || !v || !gamma || !out || B <= 0 || H <= 0 || N <= 0 || d <= 0) return 1;
+    long BH = (long)B * H;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < BH; ++bh) {
+        double *U = (double *)malloc(sizeof(double) * d * d);
+        if (!U) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        if (state_in) memcpy(U, state_in + (size_t)bh * d * d, sizeof(double) * d * d);
+        else memset(U, 0, sizeof(double) * d * d);
+        size_t base = (size_t)bh * N * d;
+        for (long i = 0; i < N; ++i)
+            recurrent_token(U, q + base + i * d, k + base + i * d, v + base + i * d,
+                            gamma[bh % H], d, out + base + i * d);
+        if (state_out) memcpy(state_out + (size_t)bh * d * d, U, sizeof(double) * d * d);
+        free(U);
+    }
+    return failed;
+}
+
+/*
+ * One decode step: q, k, v, out are [B][H][d]; state is updated in place.
+ * This is form 2 applied to a single token per (b,h).
+ */
+int leet_oracle_decode_step(const double *q, const double *k, const double *v,
+                            const double *gamma, double *state_inout, double *out,
+                            int B, int H, int d)
+{
+    if (!q || !k || !v || !gamma || !state_inout || !out || B <= 0 || H <= 0 || d <= 0) return 1;
+    long BH = (long)B * H;
+#pragma omp parallel for schedule(static)
+    for (long bh = 0; bh < BH; ++bh)
+        recurrent_token(state_inout + (size_t)bh * d * d, q + bh * d, k + bh * d,
+                        v + bh * d, gamma[bh % H], d, out + bh * d);
+    return 0;
+}
+
+int leet_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,45 @@
+"""Shared test helpers: error metrics and golden-file parsing (no operator arithmetic)."""
+import numpy as np
+
+
+def rel_err_per_head(got, ref):
+    """max|got-ref| / max|ref| per (b,h) slab; arrays are [B,H,...]. Returns [B,H]."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    B, H = ref.shape[:2]
+    g = got.reshape(B, H, -1)
+    r = ref.reshape(B, H, -1)
+    num = np.abs(g - r).max(axis=2)
+    den = np.abs(r).max(axis=2)
+    den = np.where(den > 0, den, 1.0)
+    return num / den
+
+
+def max_rel_err(got, ref):
+    """Worst (b,h) of ``rel_err_per_head``: the primary parity metric."""
+    return float(rel_err_per_head(got, ref).max())
+
+
+def elementwise_ok(got, ref, tol):
+    """Secondary metric: |got-ref| <= tol * (|ref| + rms(ref)) element by element, rms per (b,h)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    B, H = ref.shape[:2]
+    g = got.reshape(B, H, -1)
+    r = ref.reshape(B, H, -1)
+    rms = np.sqrt((r * r).mean(axis=2, keepdims=True))
+    return bool(np.all(np.abs(g - r) <= tol * (np.abs(r) + rms) + 1e-300))
+
+
+def parse_golden(path):
+    """'name a b ; c d' lines -> dict name -> 2-D float array (1-D rows for single-row entries)."""
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, rest = line.split(None, 1)
+            rows = [[float(x) for x in row.split()] for row in rest.split(";")]
+            out[name] = np.array(rows, dtype=np.float64)
+    return out

@@ -1,0 +1,128 @@
+/*
+ * leet_attn.h -- C ABI of the MI355X (gfx950) library for exponentially decaying
+ * causal linear attention.
+ *
+ * Operator (Section 2.2, Eq. "BCMV", with B = Q and C = K):
+ *
+ *     O = ((Q K^T) .* M) V,      M[i][j] = gamma^(i-j) if i >= j, else 0,
+ *
+ * one gamma per head, 0 <= gamma <= 1, 0^0 = 1 (so M[i][i] = 1 always).  There is
+ * no softmax, no row normalisation and no 1/sqrt(d) factor inside the operator.
+ * The library evaluates it in chunked ("block-based") form -- Appendix B.2, Alg. 2,
+ * carried over to the decaying mask with the row/column weight split of
+ * Appendix B.3, Alg. 4 -- and continues it token by token with the row-based
+ * recursion of Appendix B.1, Alg. 1 and the discounted update of Appendix C.1:
+ *
+ *     S <- gamma S + k^T v ;   o = q S            (S is d x d, rows = key index).
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer (HIP global memory on the current
+ *     device), 16-byte aligned, densely packed, row-major in the stated shape.
+ *   - `stream` is a hipStream_t passed as void*; NULL means the default stream.
+ *     Calls are asynchronous: they enqueue kernels on `stream` and return.  The
+ *     caller keeps every buffer alive and unmodified until the stream has
+ *     finished the work.
+ *   - The caller owns all buffers.  The library keeps no pointer after the work
+ *     is done.  `out` must not overlap any input.
+ *   - The return value is a leet_status.  On any status other than LEET_OK
+ *     nothing has been enqueued and no buffer has been written.
+ *   - d must be 64 or 128.  B, H, N >= 1.  N need not be a multiple of the
+ *     chunk length (64 tokens); the last chunk may be ragged.
+ *   - gamma outside [0, 1] is not diagnosed (the values live in device memory).
+ */
+#ifndef LEET_ATTN_H
+#define LEET_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LEET_F32 = 0, /* q, k, v are IEEE binary32; products on fp32 MFMA            */
+    LEET_BF16 = 1 /* q, k, v are bfloat16; products on bf16 MFMA, fp32 accumulate */
+} leet_dtype;
+
+typedef enum {
+    LEET_OK = 0,
+    LEET_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, misaligned pointer, workspace too small */
+    LEET_ERR_UNSUPPORTED = 2, /* d not in {64, 128}, unknown dtype, no gfx950 device */
+    LEET_ERR_LAUNCH = 3,      /* the HIP runtime refused a launch or an allocation */
+    LEET_ERR_TOO_LARGE = 4    /* sizes overflow the library's index range */
+} leet_status;
+
+/*
+ * Chunked prefill (Eq. "BCMV" via Alg. 2 + the Alg. 4 weight split), zero initial state.
+ *   q, k, v  [B][H][N][d], element type `dtype`
+ *   gamma    [H] float
+ *   out      [B][H][N][d] float (fp32 for both input types)
+ * Long sequences are cut into segments that run in parallel; the segment
+ * boundary states live in a per-device workspace that the library allocates
+ * with hipMalloc on first need and grows when a later call needs more (see
+ * leet_attn_release_workspace).  Because that workspace is shared, calls on one
+ * device must not run concurrently on different streams; use leet_attn_forward_ex
+ * with caller-owned workspaces for that.
+ */
+int leet_attn_forward(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                      int B, int H, int N, int d, int dtype, void *stream);
+
+/*
+ * One decode step (Alg. 1 with the discounted update of Appendix C.1):
+ *     S <- gamma_h S + k^T v ;  o = q S     for each (b, h).
+ *   q, k, v      [B][H][d] bfloat16
+ *   gamma        [H] float
+ *   state_inout  [B][H][d][d] float, rows = key index, cols = value index; updated in place
+ *   out          [B][H][d] float
+ */
+int leet_attn_decode_step(const void *q, const void *k, const void *v, const float *gamma,
+                          float *state_inout, float *out, int B, int H, int d, void *stream);
+
+/* As leet_attn_decode_step, with q, k, v of element type `dtype` (LEET_F32 or LEET_BF16). */
+int leet_attn_decode_step_ex(const void *q, const void *k, const void *v, const float *gamma,
+                             float *state_inout, float *out, int B, int H, int d, int dtype,
+                             void *stream);
+
+/*
+ * Chunked prefill with state hand-off (the state that Alg. 1 carries from token to token,
+ * entering and leaving the call), so that a prompt can be processed in pieces and
+ * continued by decode steps.
+ *   state_in   [B][H][d][d] float or NULL (zero state); the state before token 0
+ *   state_out  [B][H][d][d] float or NULL; receives the state after token N-1.
+ *              May alias state_in.
+ *   workspace  device buffer of at least leet_attn_workspace_bytes(B, H, N, d, dtype)
+ *              bytes, 256-byte aligned, or NULL to use the library's own per-device
+ *              workspace as leet_attn_forward does.  Its contents are scratch.
+ *   workspace_bytes  size of `workspace` (ignored when workspace is NULL)
+ *   segments   0 = let the library choose how many parallel segments to cut each
+ *              sequence into; > 0 = request that many (clamped to the number of
+ *              chunks).  The result does not depend on it beyond rounding.
+ */
+int leet_attn_forward_ex(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                         const float *state_in, float *state_out,
+                         void *workspace, size_t workspace_bytes, int segments,
+                         int B, int H, int N, int d, int dtype, void *stream);
+
+/*
+ * Bytes of workspace leet_attn_forward_ex needs for this shape with `segments`
+ * as above (0 = library's choice).  Returns 0 when no workspace is needed or the
+ * arguments are invalid.
+ */
+size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments);
+
+/*
+ * Frees the library-owned workspace of the current device (synchronises the
+ * device first).  Optional; the workspace is otherwise kept until process exit.
+ */
+int leet_attn_release_workspace(void);
+
+/* Static, never-NULL description of a leet_status value. */
+const char *leet_attn_strerror(int status);
+
+/* Library version as "major.minor.patch". */
+const char *leet_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEET_ATTN_H */

@@ -1,0 +1,216 @@
+"""ctypes binding of libleet_attn.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks shapes,
+dtypes and contiguity on the host, and passes raw device pointers plus the current
+torch stream to the C ABI declared in ``include/leet_attn.h``.  No arithmetic of the
+operator happens here, and there is no fallback: if the native library is missing the
+import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libleet_attn.so")
+
+LEET_F32, LEET_BF16 = 0, 1
+LEET_OK, LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED, LEET_ERR_LAUNCH, LEET_ERR_TOO_LARGE = 0, 1, 2, 3, 4
+
+EXPORTED_SYMBOLS = (
+    "leet_attn_forward",
+    "leet_attn_decode_step",
+    "leet_attn_decode_step_ex",
+    "leet_attn_forward_ex",
+    "leet_attn_workspace_bytes",
+    "leet_attn_release_workspace",
+    "leet_attn_strerror",
+    "leet_attn_version",
+)
+
+
+class LeetAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status}: {strerror(status)}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2501_02573_amd.build` "
+            "(there is no CPU or PyTorch fallback for this library)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.leet_attn_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+    lib.leet_attn_forward.restype = i
+    lib.leet_attn_forward_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_ex.restype = i
+    lib.leet_attn_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
+    lib.leet_attn_decode_step.restype = i
+    lib.leet_attn_decode_step_ex.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    lib.leet_attn_decode_step_ex.restype = i
+    lib.leet_attn_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.leet_attn_workspace_bytes.restype = sz
+    lib.leet_attn_release_workspace.argtypes = []
+    lib.leet_attn_release_workspace.restype = i
+    lib.leet_attn_strerror.argtypes = [i]
+    lib.leet_attn_strerror.restype = ctypes.c_char_p
+    lib.leet_attn_version.argtypes = []
+    lib.leet_attn_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.leet_attn_strerror(int(status)).decode()
+
+
+def version() -> str:
+    return lib.leet_attn_version().decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LEET_F32
+    if t.dtype == torch.bfloat16:
+        return LEET_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: q, k, v must be float32 or bfloat16")
+
+
+def _check_dev(*tensors: Optional[torch.Tensor]) -> torch.device:
+    dev = None
+    for t in tensors:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("all tensors must be GPU tensors")
+        if not t.is_contiguous():
+            raise ValueError("all tensors must be contiguous")
+        if dev is None:
+            dev = t.device
+        elif t.device != dev:
+            raise ValueError("all tensors must be on one device")
+    return dev
+
+
+def _stream_ptr(dev: torch.device) -> int:
+    return torch.cuda.current_stream(dev).cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0) -> int:
+    return int(lib.leet_attn_workspace_bytes(B, H, N, d, dtype, segments))
+
+
+def release_workspace() -> None:
+    st = lib.leet_attn_release_workspace()
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_release_workspace")
+
+
+def _check_forward(q, k, v, gamma, out):
+    if q.dim() != 4 or q.shape != k.shape or q.shape != v.shape:
+        raise ValueError("q, k, v must share one [B, H, N, d] shape")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share one dtype")
+    B, H, N, d = q.shape
+    if gamma.dtype != torch.float32 or gamma.numel() != H:
+        raise ValueError("gamma must be float32 with one value per head")
+    if out.dtype != torch.float32 or out.shape != q.shape:
+        raise ValueError("out must be float32 [B, H, N, d]")
+    return B, H, N, d
+
+
+def leet_attn_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: torch.Tensor,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Chunked prefill with zero initial state; returns fp32 ``out`` [B, H, N, d]."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, N, d = _check_forward(q, k, v, gamma, out)
+    dev = _check_dev(q, k, v, gamma, out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), B, H, N, d,
+                                   _dtype_code(q), ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward")
+    return out
+
+
+def leet_attn_forward_ex(q, k, v, gamma, out: Optional[torch.Tensor] = None,
+                         state_in: Optional[torch.Tensor] = None,
+                         state_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, segments: int = 0) -> torch.Tensor:
+    """Chunked prefill with state hand-off and optional caller-owned workspace."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, N, d = _check_forward(q, k, v, gamma, out)
+    for name, s in (("state_in", state_in), ("state_out", state_out)):
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != (B, H, d, d)):
+            raise ValueError(f"{name} must be float32 [B, H, d, d]")
+    ws_bytes = 0
+    if workspace is not None:
+        if workspace.dtype != torch.uint8:
+            raise TypeError("workspace must be a uint8 tensor")
+        ws_bytes = workspace.numel()
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out, workspace)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                      _ptr(state_out), _ptr(workspace), ws_bytes, int(segments),
+                                      B, H, N, d, _dtype_code(q), ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_ex")
+    return out
+
+
+def _check_decode(q, k, v, gamma, state, out):
+    if q.dim() != 3 or q.shape != k.shape or q.shape != v.shape:
+        raise ValueError("q, k, v must share one [B, H, d] shape")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share one dtype")
+    B, H, d = q.shape
+    if gamma.dtype != torch.float32 or gamma.numel() != H:
+        raise ValueError("gamma must be float32 with one value per head")
+    if state.dtype != torch.float32 or tuple(state.shape) != (B, H, d, d):
+        raise ValueError("state must be float32 [B, H, d, d]")
+    if out.dtype != torch.float32 or tuple(out.shape) != (B, H, d):
+        raise ValueError("out must be float32 [B, H, d]")
+    return B, H, d
+
+
+def leet_attn_decode_step(q, k, v, gamma, state, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decode step with bf16 q, k, v: ``state`` is updated in place; returns fp32 ``out`` [B, H, d]."""
+    if q.dtype != torch.bfloat16:
+        raise TypeError("leet_attn_decode_step takes bfloat16 q, k, v (use leet_attn_decode_step_ex for float32)")
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, d = _check_decode(q, k, v, gamma, state, out)
+    dev = _check_dev(q, k, v, gamma, state, out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                       B, H, d, ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_decode_step")
+    return out
+
+
+def leet_attn_decode_step_ex(q, k, v, gamma, state, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decode step with float32 or bfloat16 q, k, v."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, d = _check_decode(q, k, v, gamma, state, out)
+    dev = _check_dev(q, k, v, gamma, state, out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_decode_step_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                          B, H, d, _dtype_code(q), ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_decode_step_ex")
+    return out

@@ -1,0 +1,227 @@
+// C ABI of the library: argument validation, segment planning, workspace, launches.
+// Every step of the computation runs in the HIP kernels; nothing here touches tensor data.
+#include <mutex>
+#include <string.h>
+
+#include "../../include/leet_attn.h"
+#include "leet_common.hpp"
+
+namespace leet {
+hipError_t launch_fwd_bf16_states(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_bf16_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
+                           int nseg, int seg_tokens, int D, hipStream_t stream);
+hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
+                         float* out, int BH, int H, int D, bool bf16, hipStream_t stream);
+}  // namespace leet
+
+namespace {
+
+using leet::kChunk;
+
+// Sequences are cut into segments so that about this many workgroups exist (two
+// per compute unit of a 256-CU device), but no segment is shorter than kMinSegChunks
+// chunks: each extra segment costs one D x D fp32 state written, scanned and re-read.
+constexpr int kTargetWorkgroups = 512;
+constexpr int kMinSegChunks = 8;
+constexpr int kMaxDevices = 64;
+
+struct Plan {
+    int nseg;
+    int seg_chunks;
+    size_t ws_bytes;
+};
+
+bool make_plan(long BH, int N, int D, int segments, Plan* plan) {
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    long want;
+    if (segments > 0) {
+        want = segments;
+    } else {
+        want = (kTargetWorkgroups + BH - 1) / BH;
+        long cap = nchunks / kMinSegChunks;
+        if (cap < 1) cap = 1;
+        if (want > cap) want = cap;
+    }
+    if (want < 1) want = 1;
+    if (want > nchunks) want = nchunks;
+    const int seg_chunks = (int)((nchunks + want - 1) / want);
+    const int nseg = (nchunks + seg_chunks - 1) / seg_chunks;
+    if (BH * (long)nseg >= (1L << 31)) return false;
+    plan->nseg = nseg;
+    plan->seg_chunks = seg_chunks;
+    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * D * D * sizeof(float);
+    return true;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool shape_ok(int d, int dtype, int* status) {
+    if (dtype != LEET_F32 && dtype != LEET_BF16) { *status = LEET_ERR_UNSUPPORTED; return false; }
+    if (d != 64 && d != 128) { *status = LEET_ERR_UNSUPPORTED; return false; }
+    return true;
+}
+
+// Library-owned workspace, one per device, grown on demand.
+std::mutex g_ws_mutex;
+void* g_ws_ptr[kMaxDevices] = {nullptr};
+size_t g_ws_size[kMaxDevices] = {0};
+int g_arch_ok[kMaxDevices] = {0};  // 0 unknown, 1 gfx950, -1 other
+
+int current_device(int* dev) {
+    if (hipGetDevice(dev) != hipSuccess) return LEET_ERR_LAUNCH;
+    if (*dev < 0 || *dev >= kMaxDevices) return LEET_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_arch_ok[*dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, *dev) != hipSuccess) return LEET_ERR_LAUNCH;
+        g_arch_ok[*dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : -1;
+    }
+    return g_arch_ok[*dev] == 1 ? LEET_OK : LEET_ERR_UNSUPPORTED;
+}
+
+int own_workspace(int dev, size_t bytes, void** out) {
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_ws_size[dev] < bytes) {
+        if (g_ws_ptr[dev]) {
+            (void)hipFree(g_ws_ptr[dev]);  // waits for work that may still use it
+            g_ws_ptr[dev] = nullptr;
+            g_ws_size[dev] = 0;
+        }
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return LEET_ERR_LAUNCH;
+        }
+        g_ws_ptr[dev] = p;
+        g_ws_size[dev] = bytes;
+    }
+    *out = g_ws_ptr[dev];
+    return LEET_OK;
+}
+
+int forward_impl(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                 const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                 int segments, int B, int H, int N, int d, int dtype, void* stream) {
+    if (!q || !k || !v || !gamma || !out) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    int status = LEET_OK;
+    if (!shape_ok(d, dtype, &status)) return status;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
+        !aligned16(state_out) || (reinterpret_cast<uintptr_t>(gamma) & 3u))
+        return LEET_ERR_INVALID_ARG;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return LEET_ERR_INVALID_ARG;
+    const long BH = (long)B * H;
+    if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
+
+    Plan plan;
+    if (!make_plan(BH, N, d, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    int dev = 0;
+    status = current_device(&dev);
+    if (status != LEET_OK) return status;
+
+    void* ws = nullptr;
+    if (plan.nseg > 1) {
+        if (workspace) {
+            if (workspace_bytes < plan.ws_bytes) return LEET_ERR_INVALID_ARG;
+            ws = workspace;
+        } else {
+            status = own_workspace(dev, plan.ws_bytes, &ws);
+            if (status != LEET_OK) return status;
+        }
+    }
+
+    leet::FwdParams p;
+    p.q = q; p.k = k; p.v = v; p.gamma = gamma; p.out = out;
+    p.state_in = state_in; p.state_out = state_out;
+    p.seg_state = static_cast<float*>(ws);
+    p.H = H; p.N = N; p.nseg = plan.nseg; p.seg_chunks = plan.seg_chunks;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = dtype == LEET_BF16;
+
+    hipError_t e = bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s) : leet::launch_fwd_f32_states(p, (int)BH, d, s);
+    if (e != hipSuccess) return LEET_ERR_LAUNCH;
+    e = leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
+    if (e != hipSuccess) return LEET_ERR_LAUNCH;
+    e = bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s) : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
+    if (e != hipSuccess) return LEET_ERR_LAUNCH;
+    return LEET_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int leet_attn_forward(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                      int B, int H, int N, int d, int dtype, void* stream) {
+    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, stream);
+}
+
+int leet_attn_forward_ex(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                         const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                         int segments, int B, int H, int N, int d, int dtype, void* stream) {
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
+                        B, H, N, d, dtype, stream);
+}
+
+size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {
+    int status = LEET_OK;
+    if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(d, dtype, &status)) return 0;
+    Plan plan;
+    if (!make_plan((long)B * H, N, d, segments, &plan)) return 0;
+    return plan.ws_bytes;
+}
+
+int leet_attn_decode_step_ex(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dtype, void* stream) {
+    if (!q || !k || !v || !gamma || !state_inout || !out) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || d <= 0) return LEET_ERR_INVALID_ARG;
+    int status = LEET_OK;
+    if (!shape_ok(d, dtype, &status)) return status;
+    if (!aligned16(state_inout) || !aligned16(out) || (reinterpret_cast<uintptr_t>(gamma) & 3u) ||
+        (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
+        (reinterpret_cast<uintptr_t>(v) & 3u))
+        return LEET_ERR_INVALID_ARG;
+    const long BH = (long)B * H;
+    if (BH >= (1L << 31)) return LEET_ERR_TOO_LARGE;
+    int dev = 0;
+    status = current_device(&dev);
+    if (status != LEET_OK) return status;
+    hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, dtype == LEET_BF16,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
+int leet_attn_decode_step(const void* q, const void* k, const void* v, const float* gamma,
+                          float* state_inout, float* out, int B, int H, int d, void* stream) {
+    return leet_attn_decode_step_ex(q, k, v, gamma, state_inout, out, B, H, d, LEET_BF16, stream);
+}
+
+int leet_attn_release_workspace(void) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LEET_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_ws_ptr[dev]) {
+        if (hipFree(g_ws_ptr[dev]) != hipSuccess) return LEET_ERR_LAUNCH;
+        g_ws_ptr[dev] = nullptr;
+        g_ws_size[dev] = 0;
+    }
+    return LEET_OK;
+}
+
+const char* leet_attn_strerror(int status) {
+    switch (status) {
+        case LEET_OK: return "ok";
+        case LEET_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive size, misaligned pointer or workspace too small)";
+        case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128, dtype f32 or bf16, device gfx950)";
+        case LEET_ERR_LAUNCH: return "HIP runtime error (launch or allocation failed)";
+        case LEET_ERR_TOO_LARGE: return "sizes exceed the library's index range";
+        default: return "unknown status";
+    }
+}
+
+const char* leet_attn_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Two small HBM-bound kernels: the scan over segment boundary states, and the
+// single-token decode step.
+#include "leet_common.hpp"
+
+namespace leet {
+
+// ---------------------------------------------------------------------------------
+// Segment scan.  On entry slot s of seg_state holds the end state of segment s run
+// from a zero state, T_s = sum_j gamma^(L-1-j) k_j^T v_j (L = segment length in
+// tokens).  On exit slot s holds the true state entering segment s+1:
+//     S_in(0) = state_in or 0 ;  S_in(s+1) = gamma^L S_in(s) + T_s
+// (the block recurrence of Alg. 2 with the decay of Appendix C.1, over segments).
+// One thread per four state elements; the loop over segments is sequential.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const float* state_in,
+                                                       const float* gamma, int H, int nseg,
+                                                       int seg_tokens, int DD4, size_t total4) {
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total4) return;
+    int bh = (int)(idx / DD4);
+    int e4 = (int)(idx % DD4);
+    const float gl = (float)pow_int((double)gamma[bh % H], seg_tokens);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (state_in) acc = reinterpret_cast<const f32x4*>(state_in)[idx];
+    f32x4* slot = reinterpret_cast<f32x4*>(seg_state) + (size_t)bh * (nseg - 1) * DD4 + e4;
+    for (int s = 0; s < nseg - 1; ++s) {
+        f32x4 t = slot[(size_t)s * DD4];
+        acc = gl * acc + t;
+        slot[(size_t)s * DD4] = acc;
+    }
+}
+
+hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
+                           int nseg, int seg_tokens, int D, hipStream_t stream) {
+    if (nseg <= 1) return hipSuccess;
+    int DD4 = D * D / 4;
+    size_t total4 = (size_t)BH * DD4;
+    unsigned blocks = (unsigned)((total4 + 255) / 256);
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(blocks), dim3(256), 0, stream, seg_state, state_in, gamma, H,
+                       nseg, seg_tokens, DD4, total4);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Decode step (Alg. 1, Appendix B.1, with the discounted update of Appendix C.1):
+//     S <- gamma S + k^T v ;  o = q S        per (batch, head), S is D x D fp32.
+// One workgroup of 256 threads streams one state once: every thread issues all of
+// its 16-byte loads up front (D*D*4/256/16 of them), updates in registers, stores
+// back to the same addresses and accumulates its share of o = q S; the partial sums
+// are combined with wave shuffles and one pass through LDS.
+// Thread t: columns 4*(t % (D/4)) .. +3, rows (t / (D/4)) + RP*m, RP = 1024/D.
+// ---------------------------------------------------------------------------------
+template <int D, typename T>
+__device__ __forceinline__ float load_elem(const T* p, int i);
+template <int D>
+__device__ __forceinline__ float load_elem_bf16(const uint16_t* p, int i) { return bf16_bits_to_f32(p[i]); }
+
+template <int D, bool kBf16>
+__global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* k, const void* v,
+                                                     const float* gamma, float* state, float* out, int H) {
+    constexpr int CP = D / 4;        // threads per state row
+    constexpr int RP = 256 / CP;     // rows per pass
+    constexpr int NPASS = D / RP;    // passes (= 16-byte loads per thread)
+    __shared__ float sq[D], sk[D], sv[D];
+    __shared__ f32x4 red[4][CP];
+
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x;
+    const int c4 = tid % CP, r0 = tid / CP;
+    f32x4* Sg = reinterpret_cast<f32x4*>(state + (size_t)bh * D * D);
+
+    f32x4 s[NPASS];
+#pragma unroll
+    for (int m = 0; m < NPASS; ++m) s[m] = Sg[(size_t)(r0 + RP * m) * CP + c4];
+
+    if (tid < D) {
+        size_t off = (size_t)bh * D + tid;
+        if (kBf16) {
+            sq[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(q)[off]);
+            sk[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(k)[off]);
+            sv[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(v)[off]);
+        } else {
+            sq[tid] = reinterpret_cast<const float*>(q)[off];
+            sk[tid] = reinterpret_cast<const float*>(k)[off];
+            sv[tid] = reinterpret_cast<const float*>(v)[off];
+        }
+    }
+    const float gm = gamma[bh % H];
+    __syncthreads();
+
+    const f32x4 vv = *reinterpret_cast<const f32x4*>(&sv[4 * c4]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < NPASS; ++m) {
+        const int row = r0 + RP * m;
+        const float kr = sk[row], qr = sq[row];
+        f32x4 x = s[m];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = fmaf(gm, x[e], kr * vv[e]);
+            acc[e] = fmaf(qr, x[e], acc[e]);
+        }
+        Sg[(size_t)row * CP + c4] = x;
+    }
+
+    // combine the row groups: inside a wave (lanes CP apart), then across the four waves
+#pragma unroll
+    for (int off = CP; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
+    const int wv = tid >> 6, ln = tid & 63;
+    if (ln < CP) red[wv][ln] = acc;
+    __syncthreads();
+    if (tid < CP) {
+        f32x4 r = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+        reinterpret_cast<f32x4*>(out + (size_t)bh * D)[tid] = r;
+    }
+}
+
+hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
+                         float* out, int BH, int H, int D, bool bf16, hipStream_t stream) {
+    dim3 grid(BH), block(256);
+    if (D == 64) {
+        if (bf16) hipLaunchKernelGGL((decode_kernel<64, true>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+        else hipLaunchKernelGGL((decode_kernel<64, false>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    } else {
+        if (bf16) hipLaunchKernelGGL((decode_kernel<128, true>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+        else hipLaunchKernelGGL((decode_kernel<128, false>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace leet

@@ -1,0 +1,97 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "leet_attn.h")
+LIB = os.path.join(ROOT, "paper_2501_02573_amd", "libleet_attn.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2501_02573_amd import build
+        build.build()
+    from paper_2501_02573_amd import binding
+    return binding.lib
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(leet_attn_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_mandated_entry_points():
+    names = declared_functions()
+    assert "leet_attn_forward" in names and "leet_attn_decode_step" in names
+    assert len(names) >= 6
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2501_02573_amd import binding
+    raw = ctypes.CDLL(LIB)
+    for name in declared_functions():
+        assert hasattr(raw, name), f"{name} declared in leet_attn.h but not exported"
+        assert name in binding.EXPORTED_SYMBOLS
+
+
+def test_strerror_and_version(lib):
+    from paper_2501_02573_amd import binding
+    assert binding.strerror(0) == "ok"
+    for st in (1, 2, 3, 4, 99):
+        assert len(binding.strerror(st)) > 0
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
+
+
+def test_workspace_bytes_plan(lib):
+    from paper_2501_02573_amd import binding as b
+    # one segment -> no workspace
+    assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == 0
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 1) == 0
+    # s segments -> (s-1) boundary states of d*d floats per (b,h)
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 8) == 4 * 16 * 7 * 128 * 128 * 4
+    assert b.workspace_bytes(1, 32, 32768, 128, b.LEET_BF16, 16) == 32 * 15 * 128 * 128 * 4
+    # requests beyond the number of chunks are clamped: N=130 has 3 chunks
+    assert b.workspace_bytes(1, 1, 130, 64, b.LEET_F32, 50) == 2 * 64 * 64 * 4
+    # invalid shapes report 0
+    assert b.workspace_bytes(1, 1, 256, 96, b.LEET_F32) == 0
+    assert b.workspace_bytes(0, 1, 256, 64, b.LEET_F32) == 0
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    """These return before any device call, so fake non-null pointers are never dereferenced."""
+    from paper_2501_02573_amd import binding as b
+    p = ctypes.c_void_p(0x1000)   # 16-byte aligned, never touched
+    odd = ctypes.c_void_p(0x1004)
+    fwd = lib.leet_attn_forward
+    assert fwd(None, p, p, p, p, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, None, p, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, p, None, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, p, p, 0, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, p, p, 1, 1, -5, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, p, p, 1, 1, 64, 96, b.LEET_F32, None) == b.LEET_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, p, 1, 1, 64, 64, 7, None) == b.LEET_ERR_UNSUPPORTED
+    assert fwd(odd, p, p, p, p, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert fwd(p, p, p, p, p, 1 << 16, 1 << 16, 64, 64, b.LEET_F32, None) == b.LEET_ERR_TOO_LARGE
+    dec = lib.leet_attn_decode_step
+    assert dec(p, p, p, p, None, p, 1, 1, 64, None) == b.LEET_ERR_INVALID_ARG
+    assert dec(p, p, p, p, p, p, 1, 0, 64, None) == b.LEET_ERR_INVALID_ARG
+    assert dec(p, p, p, p, p, p, 1, 1, 32, None) == b.LEET_ERR_UNSUPPORTED
+    assert lib.leet_attn_decode_step_ex(p, p, p, p, p, p, 1, 1, 64, 5, None) == b.LEET_ERR_UNSUPPORTED
+    ex = lib.leet_attn_forward_ex
+    assert ex(p, p, p, p, p, None, None, None, 0, -1, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert ex(p, p, p, p, p, odd, None, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+
+
+def test_binding_rejects_cpu_tensors(lib):
+    import torch
+    from paper_2501_02573_amd import binding as b
+    q = torch.zeros(1, 1, 64, 64)
+    g = torch.ones(1)
+    with pytest.raises(ValueError):
+        b.leet_attn_forward(q, q, q, g, torch.empty_like(q))

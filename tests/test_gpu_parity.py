@@ -1,0 +1,246 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, same seeded inputs.
+
+Tolerances (primary metric: max|gpu-ref| / max|ref| per (batch, head), worst head):
+fp32 inputs 1e-4, bf16 inputs 2e-2 (fp32 accumulate).  The secondary element-wise
+check |gpu-ref| <= tol (|ref| + rms(ref)) guards against isolated bad elements.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import elementwise_ok, max_rel_err
+from paper_2501_02573_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2501_02573_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(*ts):
+    return tuple(t.cuda() for t in ts)
+
+
+def check(got, ref, dtype, what):
+    err = max_rel_err(got, ref)
+    say(f"  {what}: max rel err {err:.3e} (tol {TOL[dtype]:.0e})")
+    assert np.isfinite(np.asarray(got)).all(), f"{what}: non-finite output"
+    assert err <= TOL[dtype], f"{what}: {err} > {TOL[dtype]}"
+    assert elementwise_ok(got, ref, TOL[dtype]), f"{what}: element-wise bound violated"
+
+
+# ---------------------------------------------------------------- benchmark configurations
+def test_config1_tiny_f32_both_forms(B):
+    cfg = W.CONFIG1
+    say(f"case {cfg}")
+    q, k, v, gamma = W.make_forward_inputs(cfg)
+    out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    check(out, oracle.quadratic(q64, k64, v64, g64), cfg.dtype, "vs quadratic")
+    check(out, oracle.recurrent(q64, k64, v64, g64)[0], cfg.dtype, "vs recurrent")
+
+
+def test_config2_small_f32(B):
+    cfg = W.CONFIG2
+    say(f"case {cfg}")
+    q, k, v, gamma = W.make_forward_inputs(cfg)
+    out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    check(out, oracle.recurrent(q64, k64, v64, g64)[0], cfg.dtype, "vs recurrent")
+    check(out, oracle.quadratic(q64, k64, v64, g64), cfg.dtype, "vs quadratic")
+
+
+def _sample_rows(cfg, per_head=6, seed=99):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for bh in range(cfg.B * cfg.H):
+        picks = {0, cfg.N - 1, 63, 64}
+        while len(picks) < per_head + 4:
+            picks.add(int(rng.integers(0, cfg.N)))
+        rows += [[bh, i] for i in sorted(picks)]
+    return np.array(rows)
+
+
+@pytest.mark.parametrize("cfg", [W.CONFIG3, W.CONFIG4], ids=lambda c: c.name)
+def test_full_size_bf16_configs(B, cfg):
+    """Full benchmark sizes in the launch configuration bench.py times (library-chosen segments)."""
+    say(f"case {cfg}")
+    q, k, v, gamma = W.make_forward_inputs(cfg)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    out_d = B.leet_attn_forward(dq, dk, dv, dg)
+    torch.cuda.synchronize()
+    out = out_d.cpu().numpy()
+    del out_d
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    ref, _ = oracle.recurrent(q64, k64, v64, g64)
+    check(out, ref, cfg.dtype, "vs recurrent (all elements)")
+    rows = _sample_rows(cfg)
+    quad = oracle.quadratic_rows(q64, k64, v64, g64, rows)
+    got = np.stack([out.reshape(cfg.B * cfg.H, cfg.N, cfg.d)[bh, i] for bh, i in rows])
+    scale = np.abs(ref).reshape(cfg.B * cfg.H, -1).max(axis=1)[rows[:, 0]][:, None]
+    err = float((np.abs(got - quad) / scale).max())
+    say(f"  vs quadratic on {len(rows)} sampled rows: {err:.3e}")
+    assert err <= TOL[cfg.dtype]
+
+
+def test_config5_decode_256_steps(B):
+    cfg = W.CONFIG5
+    say(f"case {cfg}")
+    state0, gamma, steps = W.decode_stream(cfg)
+    S_ref = W.to_f64(state0)
+    g64 = W.to_f64(gamma)
+    S_gpu = state0.cuda()
+    dg = gamma.cuda()
+    worst = 0.0
+    for n, (q, k, v) in enumerate(steps):
+        o = B.leet_attn_decode_step(*dev(q, k, v), dg, S_gpu).cpu().numpy()
+        o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), g64, S_ref)
+        err = max_rel_err(o, o_ref)
+        worst = max(worst, err)
+        assert err <= TOL["bf16"], f"step {n}: {err}"
+    say(f"  worst step output err {worst:.3e}")
+    check(S_gpu.cpu().numpy(), S_ref, "bf16", "final state")
+    # fp32 state arithmetic on bf16-exact inputs: far tighter than the bf16 bound
+    assert worst < 1e-4 and max_rel_err(S_gpu.cpu().numpy(), S_ref) < 1e-4
+
+
+# ---------------------------------------------------------------- shapes, tails, segments, degenerate gammas
+SHAPES = [
+    # B, H, N, d, dtype, segments
+    (1, 1, 1, 64, "f32", 0),
+    (1, 2, 63, 64, "f32", 0),
+    (2, 1, 64, 64, "bf16", 0),
+    (1, 2, 65, 128, "f32", 0),
+    (1, 3, 200, 128, "bf16", 0),
+    (2, 3, 777, 64, "bf16", 3),
+    (1, 4, 777, 128, "bf16", 4),
+    (1, 4, 1000, 64, "f32", 5),
+    (1, 2, 1025, 128, "f32", 2),
+    (1, 2, 130, 64, "f32", 50),      # more segments requested than chunks: clamped
+    (3, 5, 1536, 128, "bf16", 0),
+    (1, 1, 4096, 128, "bf16", 16),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_%s_seg%d" % s)
+def test_shapes_tails_segments(B, shape):
+    Bn, H, N, d, dtype, segs = shape
+    say(f"case shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=1000 + N + d, gamma=gamma)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.1).astype(np.float32))
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    s_out = torch.empty_like(ds_in)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+
+    out = B.leet_attn_forward_ex(dq, dk, dv, dg, state_out=s_out, segments=segs).cpu().numpy()
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+    check(out, ref, dtype, "zero state: out")
+    check(s_out.cpu().numpy(), s_ref, dtype, "zero state: final state")
+
+    ws_bytes = B.workspace_bytes(Bn, H, N, d, B.LEET_F32 if dtype == "f32" else B.LEET_BF16, segs)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device="cuda")
+    out2 = B.leet_attn_forward_ex(dq, dk, dv, dg, state_in=ds_in, state_out=s_out, workspace=ws,
+                                  segments=segs).cpu().numpy()
+    ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+    check(out2, ref2, dtype, "with state_in: out")
+    check(s_out.cpu().numpy(), s_ref2, dtype, "with state_in: final state")
+
+    if segs == 0:
+        out3 = B.leet_attn_forward(dq, dk, dv, dg).cpu().numpy()
+        assert np.array_equal(out3, out), "forward and forward_ex(zero state) differ"
+
+
+def test_segment_count_does_not_change_the_result_beyond_rounding(B):
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 4, 2048, 128, "bf16", 5, W.make_gamma("pow2:5:10", 4))
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    for segs in (1, 2, 7, 32):
+        say(f"case segments={segs}")
+        out = B.leet_attn_forward_ex(dq, dk, dv, dg, segments=segs).cpu().numpy()
+        check(out, ref, "bf16", f"segments={segs}")
+
+
+# ---------------------------------------------------------------- prefill -> decode hand-off
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("n0", [128, 129])
+def test_prefill_then_decode_matches_one_prefill(B, dtype, d, n0):
+    """State carried from chunked prefill into decode steps: prefill(n0) + T steps == prefill(n0 + T)."""
+    Bn, H, T = 2, 3, 9
+    say(f"case dtype={dtype} d={d} n0={n0}")
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, n0 + T, d, dtype, seed=77 + n0)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    S = torch.empty(Bn, H, d, d, dtype=torch.float32, device="cuda")
+    B.leet_attn_forward_ex(dq[:, :, :n0].contiguous(), dk[:, :, :n0].contiguous(),
+                           dv[:, :, :n0].contiguous(), dg, state_out=S)
+    outs = []
+    for i in range(n0, n0 + T):
+        outs.append(B.leet_attn_decode_step_ex(dq[:, :, i].contiguous(), dk[:, :, i].contiguous(),
+                                               dv[:, :, i].contiguous(), dg, S).cpu().numpy())
+    dec = np.stack(outs, axis=2)
+    S_full = torch.empty_like(S)
+    full = B.leet_attn_forward_ex(dq, dk, dv, dg, state_out=S_full).cpu().numpy()
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    tail_ref = ref[:, :, n0:]
+    check(dec, tail_ref, dtype, "decode outputs vs oracle")
+    check(full[:, :, n0:], tail_ref, dtype, "prefill tail vs oracle")
+    check(S.cpu().numpy(), s_ref, dtype, "state after decode vs oracle")
+    check(S_full.cpu().numpy(), s_ref, dtype, "state after prefill vs oracle")
+    # the two GPU routes agree with each other to the same tolerance
+    assert max_rel_err(dec, full[:, :, n0:]) <= TOL[dtype]
+    assert max_rel_err(S.cpu().numpy(), S_full.cpu().numpy()) <= TOL[dtype]
+
+
+def test_decode_f32_and_d64(B):
+    for d, dtype in ((64, "bf16"), (64, "f32"), (128, "f32")):
+        say(f"case decode d={d} dtype={dtype}")
+        cfg = W.DecodeConfig("t", 3, 5, d, 7, 11, "pow2:1:9", dtype=dtype)
+        state0, gamma, steps = W.decode_stream(cfg)
+        S_ref = W.to_f64(state0); S_gpu = state0.cuda(); dg = gamma.cuda()
+        for q, k, v in steps:
+            o = B.leet_attn_decode_step_ex(*dev(q, k, v), dg, S_gpu).cpu().numpy()
+            o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), W.to_f64(gamma), S_ref)
+            assert max_rel_err(o, o_ref) < 1e-5
+        assert max_rel_err(S_gpu.cpu().numpy(), S_ref) < 1e-5
+
+
+# ---------------------------------------------------------------- determinism and error paths on the device
+def test_bitwise_determinism(B):
+    q, k, v, gamma = W.make_custom_forward_inputs(2, 4, 1500, 128, "bf16", 3)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    a = B.leet_attn_forward(dq, dk, dv, dg).cpu()
+    b = B.leet_attn_forward(dq, dk, dv, dg).cpu()
+    assert torch.equal(a, b)
+
+
+def test_errors_write_nothing(B):
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 1, 64, 64, "f32", 1)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    out = torch.full((1, 1, 64, 64), 7.0, device="cuda")
+    import ctypes
+    st = B.lib.leet_attn_forward(ctypes.c_void_p(dq.data_ptr()), ctypes.c_void_p(dk.data_ptr()),
+                                 ctypes.c_void_p(dv.data_ptr()), ctypes.c_void_p(dg.data_ptr()),
+                                 ctypes.c_void_p(out.data_ptr()), 1, 1, 64, 96, B.LEET_F32, None)
+    assert st == B.LEET_ERR_UNSUPPORTED
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.LeetAttnError) as ei:   # workspace too small for 2 segments
+        q2, k2, v2, g2 = dev(*W.make_custom_forward_inputs(1, 1, 256, 64, "f32", 2))
+        B.leet_attn_forward_ex(q2, k2, v2, g2, workspace=ws, segments=2)
+    assert ei.value.status == B.LEET_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)

@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X decayed causal linear attention library (one GPU).
+
+A step is one pass of the whole prefill hot path -- stage, scores, mask, intra and inter
+outputs, store, state update -- over one batch of the headline workload:
+B=4, H=16, N=4096, d=128, bf16 inputs, fp32 accumulate and output, per-head
+gamma_h = 1 - 2^-(5 + 3h/15), seeded synthetic q, k, v ~ N(0,1)/sqrt(d).  Inputs are
+resident in HBM before the timed region.  The decode step (config 5) and the
+long-context prefill (config 4) are timed in the same run and reported under "extra".
+
+Prints ONE JSON line.  ``value`` is tokens/s (B*N per step) of the headline workload.
+``roofline`` is for the dominant kernel (the chunk walk), whose per-launch duration is
+measured with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle
+(recurrent form) timed on this host's cores on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
+    ap.add_argument("--segments", type=int, default=0, help="0 = library's choice (the shipped configuration)")
+    return ap.parse_args()
+
+
+def alg_bytes_forward(cfg, in_bytes):
+    # per token-head: q, k, v read once + fp32 output written once
+    return cfg.B * cfg.H * cfg.N * cfg.d * (3 * in_bytes + 4)
+
+
+def alg_flops_forward(cfg):
+    # causal-exact count at chunk 64: 4 d^2 (inter + state) + 2*64*d (intra), per token-head
+    return cfg.B * cfg.H * cfg.N * (4 * cfg.d * cfg.d + 2 * 64 * cfg.d)
+
+
+def time_forward(binding, torch, q, k, v, gamma, out, steps, warmup, segments):
+    for _ in range(warmup):
+        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_times(binding, q, k, v, gamma, out, reps, segments):
+    acc = [0.0, 0.0, 0.0]
+    for _ in range(reps):
+        _, ms = binding.leet_attn_forward_profile(q, k, v, gamma, out=out, segments=segments)
+        acc = [a + m for a, m in zip(acc, ms)]
+    return [a / reps for a in acc]
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "the path shards over (batch, head) without communication, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_02573_amd import binding, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---------------- headline: config 3
+    cfg = W.CONFIG3
+    q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
+    out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
+    ms = time_forward(binding, torch, q, k, v, gamma, out, args.steps, args.warmup, args.segments)
+    kms = kernel_times(binding, q, k, v, gamma, out, max(5, min(args.steps, 50)), args.segments)
+    tokens = cfg.B * cfg.N
+    nbytes = alg_bytes_forward(cfg, 2)
+    nflops = alg_flops_forward(cfg)
+    walk_ms = kms[2]
+    result = {
+        "metric": "tokens/s, chunked decayed causal linear attention forward (B4 H16 N4096 d128 bf16)",
+        "value": tokens / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d,
+                   "chunk": 64, "segments": args.segments or "auto", "gamma": "1-2^-(5+3h/15)",
+                   "seed": cfg.seed, "out_dtype": "f32"},
+        "tflops_algorithmic": nflops / (ms * 1e-3) / 1e12,
+        "mfma_peak_frac": nflops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "hbm_frac_whole_step": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms": {"segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": kms[2]},
+        "roofline": {
+            "kernel": "fwd_bf16_kernel<128,true> (chunk walk)",
+            "bound": "hbm",
+            "achieved": nbytes / (walk_ms * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": nbytes / (walk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "traffic": None,
+            "algorithmic_bytes_per_launch": nbytes,
+            "avg_launch_ms": walk_ms,
+        },
+    }
+    del q, k, v, out
+
+    # ---------------- extra legs: long context (config 4) and decode (config 5)
+    if not args.no_extra:
+        extra = {}
+        cfg4 = W.CONFIG4
+        q, k, v, gamma4 = (t.to(dev) for t in W.make_forward_inputs(cfg4))
+        out = torch.empty((cfg4.B, cfg4.H, cfg4.N, cfg4.d), dtype=torch.float32, device=dev)
+        ms4 = time_forward(binding, torch, q, k, v, gamma4, out, max(5, args.steps // 2), max(2, args.warmup // 2), 0)
+        kms4 = kernel_times(binding, q, k, v, gamma4, out, 10, 0)
+        b4, f4 = alg_bytes_forward(cfg4, 2), alg_flops_forward(cfg4)
+        extra["long_context"] = {
+            "workload": cfg4.name, "ms_per_step": ms4, "tokens_per_s": cfg4.B * cfg4.N / (ms4 * 1e-3),
+            "tflops_algorithmic": f4 / (ms4 * 1e-3) / 1e12,
+            "hbm_frac_whole_step": b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "kernel_ms": {"segment_state_prepass": kms4[0], "segment_scan": kms4[1], "chunk_walk": kms4[2]},
+            "walk_hbm_frac": b4 / (kms4[2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+        del q, k, v, out
+
+        c5 = W.CONFIG5
+        state0, gamma5, steps_it = W.decode_stream(c5)
+        S = state0.to(dev)
+        gamma5 = gamma5.to(dev)
+        qkv = [tuple(t.to(dev) for t in next(steps_it)) for _ in range(4)]
+        o = torch.empty((c5.B, c5.H, c5.d), dtype=torch.float32, device=dev)
+        for i in range(16):
+            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, S, o)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(c5.steps):
+            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, S, o)
+        e1.record()
+        torch.cuda.synchronize()
+        ms5 = e0.elapsed_time(e1) / c5.steps
+        b5 = c5.B * c5.H * (2 * c5.d * c5.d * 4 + 3 * c5.d * 2 + c5.d * 4)
+        extra["decode"] = {
+            "workload": c5.name, "us_per_step": ms5 * 1e3, "tokens_per_s": c5.B / (ms5 * 1e-3),
+            "roofline": {"kernel": "decode_kernel<128,true>", "bound": "hbm",
+                         "achieved": b5 / (ms5 * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes_per_launch": b5,
+                         "note": "the 128 MiB state fits the 256 MB Infinity Cache"},
+        }
+        result["extra"] = extra
+        del S, qkv, o
+
+    # ---------------- CPU baseline: the oracle as it stands, on this host's cores
+    if not args.no_cpu_baseline:
+        import oracle
+        qc, kc, vc, gc = W.make_forward_inputs(cfg)
+        q64, k64, v64, g64 = (W.to_f64(t) for t in (qc, kc, vc, gc))
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.recurrent(q64, k64, v64, g64)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {
+            "value": tokens / best, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"whole {cfg.name} workload, fp64 recurrent form (Alg. 1 with decay), best of 3, {best:.2f} s",
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

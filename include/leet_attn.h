@@ -24,8 +24,10 @@
  *     finished the work.
  *   - The caller owns all buffers.  The library keeps no pointer after the work
  *     is done.  `out` must not overlap any input.
- *   - The return value is a leet_status.  On any status other than LEET_OK
- *     nothing has been enqueued and no buffer has been written.
+ *   - The return value is a leet_status.  Arguments are validated on the host
+ *     before anything is enqueued: on LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED and
+ *     LEET_ERR_TOO_LARGE no buffer has been written.  LEET_ERR_LAUNCH means the HIP
+ *     runtime failed part-way; the contents of the output buffers are then undefined.
  *   - d must be 64 or 128.  B, H, N >= 1.  N need not be a multiple of the
  *     chunk length (64 tokens); the last chunk may be ragged.
  *   - gamma outside [0, 1] is not diagnosed (the values live in device memory).
@@ -102,6 +104,20 @@ int leet_attn_forward_ex(const void *q, const void *k, const void *v, const floa
                          const float *state_in, float *state_out,
                          void *workspace, size_t workspace_bytes, int segments,
                          int B, int H, int N, int d, int dtype, void *stream);
+
+/*
+ * Measurement aid: exactly leet_attn_forward_ex, but HIP events are recorded on `stream`
+ * around each of the three kernels a prefill launches and the call waits for them.
+ *   kernel_ms  HOST pointer to 3 floats, filled with the milliseconds of
+ *              [0] the segment-state pre-pass, [1] the segment scan, [2] the chunk walk
+ *              ([0] and [1] are 0 when the plan has a single segment).
+ * Synchronous (returns after the work has finished); not for use under graph capture.
+ */
+int leet_attn_forward_profile(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                              const float *state_in, float *state_out,
+                              void *workspace, size_t workspace_bytes, int segments,
+                              int B, int H, int N, int d, int dtype, void *stream,
+                              float *kernel_ms);
 
 /*
  * Bytes of workspace leet_attn_forward_ex needs for this shape with `segments`

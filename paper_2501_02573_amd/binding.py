@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_decode_step",
     "leet_attn_decode_step_ex",
     "leet_attn_forward_ex",
+    "leet_attn_forward_profile",
     "leet_attn_workspace_bytes",
     "leet_attn_release_workspace",
     "leet_attn_strerror",
@@ -49,6 +50,9 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_forward.restype = i
     lib.leet_attn_forward_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp]
     lib.leet_attn_forward_ex.restype = i
+    lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
+                                              ctypes.POINTER(ctypes.c_float)]
+    lib.leet_attn_forward_profile.restype = i
     lib.leet_attn_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.leet_attn_decode_step.restype = i
     lib.leet_attn_decode_step_ex.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
@@ -169,6 +173,22 @@ def leet_attn_forward_ex(q, k, v, gamma, out: Optional[torch.Tensor] = None,
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_forward_ex")
     return out
+
+
+def leet_attn_forward_profile(q, k, v, gamma, out: Optional[torch.Tensor] = None, segments: int = 0):
+    """One prefill with per-kernel HIP-event timing; returns (out, [pre-pass ms, scan ms, walk ms])."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, N, d = _check_forward(q, k, v, gamma, out)
+    dev = _check_dev(q, k, v, gamma, out)
+    ms = (ctypes.c_float * 3)()
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_profile(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), None, None,
+                                           None, 0, int(segments), B, H, N, d, _dtype_code(q),
+                                           ctypes.c_void_p(_stream_ptr(dev)), ms)
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_profile")
+    return out, [float(x) for x in ms]
 
 
 def _check_decode(q, k, v, gamma, state, out):

@@ -104,7 +104,7 @@ int own_workspace(int dev, size_t bytes, void** out) {
 
 int forward_impl(const void* q, const void* k, const void* v, const float* gamma, float* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
-                 int segments, int B, int H, int N, int d, int dtype, void* stream) {
+                 int segments, int B, int H, int N, int d, int dtype, void* stream, float* kernel_ms) {
     if (!q || !k || !v || !gamma || !out) return LEET_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
@@ -141,13 +141,37 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = dtype == LEET_BF16;
 
+    // Optional per-kernel timing: HIP events on the launch stream between the three launches.
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    if (kernel_ms) {
+        for (int i = 0; i < 4; ++i)
+            if (hipEventCreate(&ev[i]) != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+                return LEET_ERR_LAUNCH;
+            }
+        (void)hipEventRecord(ev[0], s);
+    }
     hipError_t e = bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s) : leet::launch_fwd_f32_states(p, (int)BH, d, s);
-    if (e != hipSuccess) return LEET_ERR_LAUNCH;
-    e = leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
-    if (e != hipSuccess) return LEET_ERR_LAUNCH;
-    e = bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s) : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
-    if (e != hipSuccess) return LEET_ERR_LAUNCH;
-    return LEET_OK;
+    if (e == hipSuccess) {
+        if (kernel_ms) (void)hipEventRecord(ev[1], s);
+        e = leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
+    }
+    if (e == hipSuccess) {
+        if (kernel_ms) (void)hipEventRecord(ev[2], s);
+        e = bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s) : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
+    }
+    int rc = (e == hipSuccess) ? LEET_OK : LEET_ERR_LAUNCH;
+    if (kernel_ms) {
+        if (rc == LEET_OK) {
+            (void)hipEventRecord(ev[3], s);
+            if (hipEventSynchronize(ev[3]) != hipSuccess) rc = LEET_ERR_LAUNCH;
+            for (int i = 0; i < 3 && rc == LEET_OK; ++i)
+                if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = LEET_ERR_LAUNCH;
+            if (plan.nseg <= 1) kernel_ms[0] = kernel_ms[1] = 0.0f;  // nothing was launched in those slots
+        }
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+    }
+    return rc;
 }
 
 }  // namespace
@@ -156,14 +180,23 @@ extern "C" {
 
 int leet_attn_forward(const void* q, const void* k, const void* v, const float* gamma, float* out,
                       int B, int H, int N, int d, int dtype, void* stream) {
-    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, stream);
+    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, stream, nullptr);
 }
 
 int leet_attn_forward_ex(const void* q, const void* k, const void* v, const float* gamma, float* out,
                          const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
                          int segments, int B, int H, int N, int d, int dtype, void* stream) {
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, dtype, stream);
+                        B, H, N, d, dtype, stream, nullptr);
+}
+
+int leet_attn_forward_profile(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                              const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                              int segments, int B, int H, int N, int d, int dtype, void* stream,
+                              float* kernel_ms) {
+    if (!kernel_ms) return LEET_ERR_INVALID_ARG;
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
+                        B, H, N, d, dtype, stream, kernel_ms);
 }
 
 size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {

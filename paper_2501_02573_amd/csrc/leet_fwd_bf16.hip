@@ -8,51 +8,68 @@
 //     O_t     = ((Q_t K_t^T) .* D) V_t + Lam (Q_t S_t)       D[i][j] = gamma^(i-j), i >= j
 //     S_{t+1} = gamma^L S_t + (Gam K_t)^T V_t                Lam = diag(gamma^(i+1)), Gam = diag(gamma^(L-1-j))
 //
-// Work split: wave w owns value columns [32w, 32w+32).  It keeps S[:, cols] (D x 32
-// fp32) in accumulators for the whole walk and computes O_t[:, cols]; every wave
-// recomputes the 64 x 64 score tile, which keeps the waves independent of one
-// another between the two barriers that stage a chunk into LDS.
+// Work split: wave w owns value columns [32w, 32w+32): it keeps S[:, cols] (D x 32
+// fp32) in accumulators for the whole walk and computes O_t[:, cols].  The 64 x 64
+// score matrix has three non-zero 32 x 32 tiles; each is computed once per workgroup
+// (tile n by wave n mod #waves), masked, packed to bf16 and handed to the other waves
+// through a small LDS buffer laid out in operand-register order.
 //
-// Register-level chaining (no LDS round trip for P or S):
-//  * scores are produced transposed, P^T = K Q^T, so that the accumulator layout of
-//    P^T (lane = query row, registers = keys) is already the A-operand layout of P
-//    for P V, up to a fixed permutation of the contraction index that the V operand
-//    read applies as well;
-//  * S accumulators (lane = value column, registers = key rows) are the B-operand
-//    layout for Q S, again up to a permutation of the contraction index that the Q
-//    operand read applies.
-// Accumulator layout of a 32x32 tile: lane l holds column l%32 and, in register r,
-// row 8*(r/4) + 4*(l/32) + r%4.  A/B operand layout: lane l holds row (A) or column
-// (B) l%32 and contraction indices 8*(l/32) .. 8*(l/32)+7.
+// MFMA conventions (32x32x16): an A (B) operand register set holds, in lane l, row
+// (column) l%32 and the eight contraction slots of group g = l/32; an accumulator
+// holds, in lane l, column l%32 and, in register r, row m(r, g) = 8(r/4) + 4g + r%4.
+// A contraction may use any assignment of indices to slots as long as A and B agree.
+//
+// Data flow per chunk; Q, K, V sit row-major in LDS and are never transposed in memory:
+//   G1  P^T[j][i]  = sum_dk K[j][dk] Q[i][dk]        A = K rows, B = Q rows (16-byte LDS reads)
+//       P^T       *= D^T                             per-lane weights, fixed for the kernel
+//   G3  O^T[c][i]  = sum_dk S^T[c][dk] Q^T[dk][i]    A = S accumulators (packed to bf16), B = Q rows
+//       O^T       *= gamma^(i+1)                     one scalar per lane, since lane = token
+//   G2  O^T[c][i] += sum_j V^T[c][j] P^T[j][i]       A = V through transposing LDS reads
+//                                                    (ds_read_b64_tr_b16), B = packed P^T
+//   G4  S[dk][c]  += sum_j K^T[dk][j] (Gam V)[j][c]  A = K through transposing LDS reads,
+//                                                    B = the V fragments of G2, scaled by Gam
+// P^T accumulators (lane = query, registers = keys) are already a B operand, and S
+// accumulators (lane = value column, registers = key rows) are already an A operand,
+// so neither is ever re-laid out.  G4 assigns key-dimension index dk = 32t + pi(m) to
+// accumulator row m of tile t, pi swapping bits 2 and 3 of m; then registers 8h..8h+7
+// of a lane hold the eight consecutive dk = 32t + 16h + 8g + e that G3 contracts
+// against one 16-byte Q fragment.
+//
+// A ragged last chunk (L < 64) is right-aligned in the tile: rows 64-L.. hold the
+// tokens, rows above are zero.  The intra-chunk weights depend on i-j only and Gam on
+// 63-j', so both stay valid; only Lam and gamma^L are taken from the table.
 #include "leet_common.hpp"
 
 namespace leet {
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
 template <int D>
 struct Bf16Smem {
-    static constexpr int QS = D + 8;  // padded row stride (elements): 16-byte reads of 32 rows spread over all banks
-    uint16_t q[kChunk * QS];          // Q_t   [i][dk]
-    uint16_t k[kChunk * QS];          // K_t   [j][dk]
-    uint16_t kt[D * kChunk];          // (Gam K_t)^T [dk][j], 16-byte slots XOR-swizzled
-    uint16_t vt[D * kChunk];          // V_t^T [c][j], same swizzle
-    float pw[kChunk + 4];             // gamma^n, n = 0..64
+    static constexpr int RSQ = D + 8;   // row strides (elements): 16-byte row reads of 32 rows spread over the banks
+    static constexpr int RSK = D + 8;
+    static constexpr int RSV = D + 16;  // V is only read through ds_read_b64_tr_b16 (4 rows x 32 B per 16 lanes)
+    uint16_t q[kChunk * RSQ];           // Q_t [i][dk]
+    uint16_t k[kChunk * RSK];           // K_t [j][dk]
+    uint16_t v[kChunk * RSV];           // V_t [j][c]
+    u32x4 pfrag[3][2][64];              // masked P^T tiles as B operands: [tile][register half][lane]
+    float pw[kChunk + 4];               // gamma^n, n = 0..64
+    float gw[kChunk];                   // gamma^(63-j)
 };
-
-// Element offset of (row, j) inside a transposed tile: rows are 64 elements (128 B,
-// eight 16-byte slots); the slot index is XORed with a row hash so that both the
-// column-wise staging writes and the row-wise operand reads spread over the banks.
-__device__ __forceinline__ int tr_off(int row, int j) {
-    int slot = (j >> 3) ^ ((row ^ (row >> 3)) & 7);
-    return row * kChunk + slot * 8 + (j & 7);
-}
 
 __device__ __forceinline__ bf16x8 frag16(const uint16_t* p) {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p));
 }
 
-__device__ __forceinline__ bf16x8 frag8x2(const uint16_t* p0, const uint16_t* p1) {
-    u32x2 a = *reinterpret_cast<const u32x2*>(p0);
-    u32x2 b = *reinterpret_cast<const u32x2*>(p1);
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element i%4 of
+// the 8-byte rows addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4 of the group.
+__device__ __forceinline__ u32x2 lds_tr(const uint16_t* p) {
+    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(const_cast<uint16_t*>(p)));
+    return __builtin_bit_cast(u32x2, r);
+}
+
+__device__ __forceinline__ bf16x8 join(u32x2 a, u32x2 b) {
     u32x4 r = {a.x, a.y, b.x, b.y};
     return __builtin_bit_cast(bf16x8, r);
 }
@@ -65,27 +82,33 @@ __device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int h) {
     return r;
 }
 
-template <int D>
-struct StageMap {
-    static constexpr int PR = D / 8;       // 16-byte pieces per row
-    static constexpr int RW = 64 / PR;     // rows covered by one wave-wide load
-    int cc;                                // piece index within the row
-    int jbase;                             // row of load r is jbase + (r&1) + 2*RW*(r>>1)
-    __device__ StageMap(int tid) {
-        int w = tid >> 6, l = tid & 63;
-        cc = l % PR;
-        jbase = w * (4 * RW) + 2 * (l / PR);
+// eight bf16 values times eight fp32 weights -> bf16
+__device__ __forceinline__ bf16x8 scale8(bf16x8 x, f32x4 w0, f32x4 w1) {
+    u32x4 u = __builtin_bit_cast(u32x4, x);
+    bf16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        uint32_t word = u[e >> 1];
+        float f = (e & 1) ? __uint_as_float(word & 0xffff0000u) : __uint_as_float(word << 16);
+        float wgt = (e < 4) ? w0[e & 3] : w1[e & 3];
+        r[e] = (__bf16)(f * wgt);
     }
-    __device__ __forceinline__ int row(int r) const { return jbase + (r & 1) + 2 * RW * (r >> 1); }
-};
+    return r;
+}
+
+// Score tiles in production order: tile 0 = (jt 0, it 0), tile 1 = (jt 1, it 1), tile 2 = (jt 0, it 1).
+__device__ __forceinline__ constexpr int tile_jt(int n) { return n == 1 ? 1 : 0; }
+__device__ __forceinline__ constexpr int tile_it(int n) { return n == 0 ? 0 : 1; }
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment
 // pre-pass: the end state of a segment started from zero).
 template <int D, bool kOut>
-__global__ __launch_bounds__(D * 2) void fwd_bf16_kernel(FwdParams p) {
-    constexpr int NW = D / 32;   // waves = 32-column slices
+__global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
+    constexpr int NT = D * 2;    // threads: one wave per 32 value columns
+    constexpr int NW = D / 32;   // waves
     constexpr int DT = D / 32;   // 32-row tiles of the key dimension
-    constexpr int QS = Bf16Smem<D>::QS;
+    constexpr int PR = D / 8;    // 16-byte pieces per row
+    constexpr int RSQ = Bf16Smem<D>::RSQ, RSK = Bf16Smem<D>::RSK, RSV = Bf16Smem<D>::RSV;
     __shared__ __attribute__((aligned(16))) Bf16Smem<D> sm;
 
     const int tid = threadIdx.x;
@@ -105,38 +128,84 @@ __global__ __launch_bounds__(D * 2) void fwd_bf16_kernel(FwdParams p) {
     const uint16_t* vb = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
     float* ob = p.out + seq_off;
 
-    // decay table, fp64 -> fp32 once per workgroup
+    // decay tables, fp64 -> fp32 once per workgroup
     {
         const double gd = (double)p.gamma[h];
-        for (int n = tid; n <= kChunk; n += D * 2) sm.pw[n] = (float)pow_int(gd, n);
+        for (int n = tid; n <= kChunk; n += NT) {
+            float x = (float)pow_int(gd, n);
+            sm.pw[n] = x;
+            if (n < kChunk) sm.gw[kChunk - 1 - n] = x;
+        }
     }
 
-    // state slice S[:, 32w .. 32w+31]
+    // state slice: S[t][r] = S[dk = 32t + pi(m(r, g))][c = 32w + ln]
     f32x16 S[DT];
     const int c_own = 32 * w + ln;
+    auto dk_of = [&](int t, int r) {
+        // m = 8(r/4) + 4g + r%4 ; pi swaps the 4- and 8-bits: dk = 16(r/8) + 8g + 4((r/4)&1) + r%4
+        return 32 * t + 16 * (r >> 3) + 8 * g + 4 * ((r >> 2) & 1) + (r & 3);
+    };
     {
         const float* src = nullptr;
         if (kOut) {
             if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
             else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * D;
         }
+        if (src) {
 #pragma unroll
-        for (int t = 0; t < DT; ++t)
+            for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int dk = 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                S[t][r] = src ? src[dk * D + c_own] : 0.0f;
-            }
+                for (int r = 0; r < 16; ++r) S[t][r] = src[dk_of(t, r) * D + c_own];
+        } else {
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[t][r] = 0.0f;
+        }
     }
 
-    const StageMap<D> sm_map(tid);
+    // ---- per-lane LDS bases; every fragment address below is one of these plus a constant
+    const int s16 = l & 15, half = (l >> 4) & 1;
+    const uint16_t* q_row = &sm.q[ln * RSQ + 8 * g];   // + 32*it*RSQ + 16*s
+    const uint16_t* k_row = &sm.k[ln * RSK + 8 * g];   // + 32*jt*RSK + 16*s
+    // transposing reads: lane supplies row 4g + s16/4 (+ 8*rd + 16*f) and four consecutive columns
+    const uint16_t* v_tr = &sm.v[(4 * g + (s16 >> 2)) * RSV + 32 * w + 16 * half + 4 * (s16 & 3)];
+    const uint16_t* k_tr = &sm.k[(4 * g + (s16 >> 2)) * RSK + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1)];
+
+    __syncthreads();  // tables visible
+
+    // ---- per-lane constants of the walk: decay weights of the score tiles this wave produces.
+    // wgt[0]: a tile on the diagonal (i - j = ln - jr, zero above the diagonal);
+    // wgt[1]: the tile below it (i - j = 32 + ln - jr).  With four waves each wave needs one set.
+    constexpr bool kBothSets = NW < 3;
+    f32x16 wgt[kBothSets ? 2 : 1];
+    float lam_full[2];  // gamma^(i+1) for a full chunk
+    if (kOut) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int n = ln - (8 * (r >> 2) + 4 * g + (r & 3));
+            float diag = (n >= 0) ? sm.pw[max(n, 0)] : 0.0f;
+            float below = sm.pw[32 + n];
+            if (kBothSets) {
+                wgt[0][r] = diag;
+                wgt[kBothSets ? 1 : 0][r] = below;
+            } else {
+                wgt[0][r] = (w == 2) ? below : diag;
+            }
+        }
+        lam_full[0] = sm.pw[ln + 1];
+        lam_full[1] = sm.pw[32 + ln + 1];
+    }
+
     u32x4 rq[4], rk[4], rv[4];
     auto prefetch = [&](int tok0) {
+        const int shift = max(0, tok0 + kChunk - tok_end);  // rows [0, shift) of the tile stay zero
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            int j = sm_map.row(r);
-            bool ok = tok0 + j < tok_end;
-            size_t off = (size_t)(tok0 + j) * D + sm_map.cc * 8;
+            int piece = r * NT + tid;
+            int j = piece / PR, cc = piece % PR;
+            bool ok = j >= shift;
+            size_t off = (size_t)(tok0 - shift + j) * D + cc * 8;
             u32x4 z = {0u, 0u, 0u, 0u};
             if (kOut) rq[r] = ok ? *reinterpret_cast<const u32x4*>(qb + off) : z;
             rk[r] = ok ? *reinterpret_cast<const u32x4*>(kb + off) : z;
@@ -145,103 +214,101 @@ __global__ __launch_bounds__(D * 2) void fwd_bf16_kernel(FwdParams p) {
     };
 
     prefetch(tok_begin);
-    __syncthreads();  // pw visible
 
     for (int t = 0; t < nchunks; ++t) {
         const int tok0 = tok_begin + t * kChunk;
         const int Lc = min(kChunk, tok_end - tok0);
+        const int shift = kChunk - Lc;
 
-        if (t > 0) __syncthreads();  // everyone is done reading the previous chunk's tiles
-        // ---- registers -> LDS (row-major Q, K; transposed, Gam-scaled K; transposed V)
+        if (t > 0) __syncthreads();  // everyone is done reading the previous chunk's tiles and P fragments
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int j = sm_map.row(r);
-            const int cc = sm_map.cc;
-            if (kOut) {
-                *reinterpret_cast<u32x4*>(&sm.q[j * QS + cc * 8]) = rq[r];
-                *reinterpret_cast<u32x4*>(&sm.k[j * QS + cc * 8]) = rk[r];
-            }
-            const float sc = sm.pw[max(Lc - 1 - j, 0)];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                uint32_t kw = rk[r][e >> 1], vw = rv[r][e >> 1];
-                uint32_t kbits = (e & 1) ? (kw >> 16) : (kw & 0xffffu);
-                uint32_t vbits = (e & 1) ? (vw >> 16) : (vw & 0xffffu);
-                __bf16 ks = (__bf16)(bf16_bits_to_f32(kbits) * sc);
-                sm.kt[tr_off(cc * 8 + e, j)] = __builtin_bit_cast(uint16_t, ks);
-                sm.vt[tr_off(cc * 8 + e, j)] = (uint16_t)vbits;
-            }
+            int piece = r * NT + tid;
+            int j = piece / PR, cc = piece % PR;
+            if (kOut) *reinterpret_cast<u32x4*>(&sm.q[j * RSQ + cc * 8]) = rq[r];
+            *reinterpret_cast<u32x4*>(&sm.k[j * RSK + cc * 8]) = rk[r];
+            *reinterpret_cast<u32x4*>(&sm.v[j * RSV + cc * 8]) = rv[r];
         }
         __syncthreads();
         if (t + 1 < nchunks) prefetch(tok0 + kChunk);  // in flight during the MFMA work below
 
+        f32x16 o[2];
         if (kOut) {
-            f32x16 o[2];
+            // G1 + mask for the score tiles this wave produces
+#pragma unroll
+            for (int n = 0; n < 3; ++n) {
+                if (n % NW != w) continue;
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < D / 16; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag16(k_row + 32 * tile_jt(n) * RSK + 16 * s),
+                                                                 frag16(q_row + 32 * tile_it(n) * RSQ + 16 * s),
+                                                                 acc, 0, 0, 0);
+                const f32x16& wt = wgt[(kBothSets && n == 2) ? 1 : 0];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] *= wt[r];
+                sm.pfrag[n][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
+                sm.pfrag[n][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
+            }
+
+            // G3: O^T = S^T Q^T, rows of O scaled by gamma^(i+1)
+            float lam[2] = {lam_full[0], lam_full[1]};
+            if (shift) {
+                lam[0] = sm.pw[max(ln + 1 - shift, 0)];
+                lam[1] = sm.pw[max(32 + ln + 1 - shift, 0)];
+            }
 #pragma unroll
             for (int it = 0; it < 2; ++it)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[it][r] = 0.0f;
-
-            // ---- inter-chunk term: O = Q_t S_t, then rows scaled by gamma^(i+1)
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int s = 0; s < D / 16; ++s) {
+                const bf16x8 sa = pack_half(S[s >> 1], s & 1);
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const bf16x8 sb = pack_half(S[dt], hh);
-                    const int dk0 = 32 * dt + 16 * hh + 4 * g;
-#pragma unroll
-                    for (int it = 0; it < 2; ++it) {
-                        const uint16_t* row = &sm.q[(32 * it + ln) * QS + dk0];
-                        o[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag8x2(row, row + 8), sb, o[it], 0, 0, 0);
-                    }
-                }
+                for (int it = 0; it < 2; ++it)
+                    o[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, frag16(q_row + 32 * it * RSQ + 16 * s), o[it],
+                                                                   0, 0, 0);
+            }
 #pragma unroll
             for (int it = 0; it < 2; ++it)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int i = 32 * it + 8 * (r >> 2) + 4 * g + (r & 3);
-                    o[it][r] *= sm.pw[i + 1];
-                }
-
-            // ---- intra-chunk term: P^T = K Q^T, decay mask, O += P V
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int jt = 0; jt <= it; ++jt) {
-                    f32x16 acc;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-                    for (int s = 0; s < D / 16; ++s) {
-                        bf16x8 a = frag16(&sm.k[(32 * jt + ln) * QS + 16 * s + 8 * g]);
-                        bf16x8 b = frag16(&sm.q[(32 * it + ln) * QS + 16 * s + 8 * g]);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        int n = 32 * (it - jt) + ln - (8 * (r >> 2) + 4 * g + (r & 3));  // i - j
-                        float wgt = sm.pw[max(n, 0)];
-                        acc[r] = (n >= 0) ? acc[r] * wgt : 0.0f;
-                    }
-#pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        const int j0 = 32 * jt + 16 * hh + 4 * g;
-                        bf16x8 b = frag8x2(&sm.vt[tr_off(c_own, j0)], &sm.vt[tr_off(c_own, j0 + 8)]);
-                        o[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pack_half(acc, hh), b, o[it], 0, 0, 0);
-                    }
-                }
-
-            // ---- store O_t[:, cols]: per register, 32 lanes write 128 contiguous bytes of one row
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int i = 32 * it + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (i < Lc) ob[(size_t)(tok0 + i) * D + c_own] = o[it][r];
-                }
+                for (int r = 0; r < 16; ++r) o[it][r] *= lam[it];
         }
 
-        // ---- state update: S = gamma^L S + (Gam K)^T V
+        // V fragments: vf[f], f = 2*jt + hh, holds keys 16f + {4g..4g+3, 8+4g..8+4g+3} of column c_own
+        bf16x8 vf[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+            vf[f] = join(lds_tr(v_tr + (16 * f) * RSV), lds_tr(v_tr + (16 * f + 8) * RSV));
+
+        if (kOut) {
+            __syncthreads();  // P fragments visible
+            // G2: O^T += V^T P^T over the tiles (jt <= it)
+#pragma unroll
+            for (int n = 0; n < 3; ++n)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+                    o[tile_it(n)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        vf[2 * tile_jt(n) + hh], __builtin_bit_cast(bf16x8, sm.pfrag[n][hh][l]), o[tile_it(n)], 0, 0, 0);
+
+            // store O^T: lane = token 32it + ln, registers 4q..4q+3 = columns 32w + 8q + 4g + (0..3)
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int i = 32 * it + ln;
+                if (i >= shift) {
+                    float* orow = ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
+                        *reinterpret_cast<f32x4*>(orow + 8 * qd) = val;
+                    }
+                }
+            }
+        }
+
+        // G4: S = gamma^L S + K^T (Gam V)
         {
             const float gl = sm.pw[Lc];
 #pragma unroll
@@ -249,13 +316,14 @@ __global__ __launch_bounds__(D * 2) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) S[dt][r] *= gl;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int j0 = 16 * s + 8 * g;
-                bf16x8 b = frag16(&sm.vt[tr_off(c_own, j0)]);
+            for (int f = 0; f < 4; ++f) {
+                const f32x4 w0 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 4 * g]);
+                const f32x4 w1 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 8 + 4 * g]);
+                const bf16x8 vs = scale8(vf[f], w0, w1);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    bf16x8 a = frag16(&sm.kt[tr_off(32 * dt + ln, j0)]);
-                    S[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, S[dt], 0, 0, 0);
+                    bf16x8 a = join(lds_tr(k_tr + (16 * f) * RSK + 32 * dt), lds_tr(k_tr + (16 * f + 8) * RSK + 32 * dt));
+                    S[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vs, S[dt], 0, 0, 0);
                 }
             }
         }
@@ -272,10 +340,7 @@ __global__ __launch_bounds__(D * 2) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
         for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int dk = 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                dst[dk * D + c_own] = S[t][r];
-            }
+            for (int r = 0; r < 16; ++r) dst[dk_of(t, r) * D + c_own] = S[t][r];
     }
 }
 

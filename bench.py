@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
     ap.add_argument("--segments", type=int, default=0, help="0 = library's choice (the shipped configuration)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the plain 1 GiB copy kernel once (known traffic, for scaling profiler byte counters)")
     return ap.parse_args()
 
 
@@ -67,6 +69,18 @@ def kernel_times(binding, q, k, v, gamma, out, reps, segments):
         _, ms = binding.leet_attn_forward_profile(q, k, v, gamma, out=out, segments=segments)
         acc = [a + m for a, m in zip(acc, ms)]
     return [a / reps for a in acc]
+
+
+def load_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed profiler summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+        ent = rec.get(workload)
+        return None if ent is None else ent.get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def main():
@@ -122,12 +136,20 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": nbytes / (walk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": load_traffic(cfg.name),
             "algorithmic_bytes_per_launch": nbytes,
             "avg_launch_ms": walk_ms,
         },
     }
     del q, k, v, out
+
+    if args.calibrate:
+        nb = 1 << 30
+        a = torch.zeros(nb // 4, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        binding.calibration_stream("copy", a, b, nb, 65536)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---------------- extra legs: long context (config 4) and decode (config 5)
     if not args.no_extra:

@@ -120,6 +120,20 @@ int leet_attn_forward_profile(const void *q, const void *k, const void *v, const
                               float *kernel_ms);
 
 /*
+ * Measurement aid: a plain streaming kernel of known traffic, used to calibrate the
+ * profiler's HBM byte counters and to find the practical streaming rate of the device.
+ *   mode 0  copy: reads `bytes` from src, writes `bytes` to dst
+ *   mode 1  read: reads `bytes` from src; dst receives one float per workgroup
+ *           (dst must hold `workgroups` floats)
+ *   mode 2  fill: writes `bytes` to dst (src ignored)
+ *   bytes   multiple of 16; src, dst 16-byte aligned device pointers
+ *   workgroups  grid size (256 threads each); each thread strides over the buffer
+ * Asynchronous on `stream`.  Not part of the attention path.
+ */
+int leet_attn_calibration_stream(int mode, const void *src, void *dst, size_t bytes, int workgroups,
+                                 void *stream);
+
+/*
  * Bytes of workspace leet_attn_forward_ex needs for this shape with `segments`
  * as above (0 = library's choice).  Returns 0 when no workspace is needed or the
  * arguments are invalid.

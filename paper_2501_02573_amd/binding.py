@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_decode_step_ex",
     "leet_attn_forward_ex",
     "leet_attn_forward_profile",
+    "leet_attn_calibration_stream",
     "leet_attn_workspace_bytes",
     "leet_attn_release_workspace",
     "leet_attn_strerror",
@@ -53,6 +54,8 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
+    lib.leet_attn_calibration_stream.argtypes = [i, vp, vp, sz, i, vp]
+    lib.leet_attn_calibration_stream.restype = i
     lib.leet_attn_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     lib.leet_attn_decode_step.restype = i
     lib.leet_attn_decode_step_ex.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
@@ -189,6 +192,18 @@ def leet_attn_forward_profile(q, k, v, gamma, out: Optional[torch.Tensor] = None
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_forward_profile")
     return out, [float(x) for x in ms]
+
+
+def calibration_stream(mode: str, src: Optional[torch.Tensor], dst: torch.Tensor, nbytes: int,
+                       workgroups: int = 4096) -> None:
+    """Launches the plain copy / read / fill kernel over ``nbytes`` (measurement aid)."""
+    code = {"copy": 0, "read": 1, "fill": 2}[mode]
+    dev = _check_dev(src, dst)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_calibration_stream(code, _ptr(src), _ptr(dst), int(nbytes), int(workgroups),
+                                              ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_calibration_stream")
 
 
 def _check_decode(q, k, v, gamma, state, out):

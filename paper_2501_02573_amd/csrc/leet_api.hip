@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation, segment planning, workspace, launches.
 // Every step of the computation runs in the HIP kernels; nothing here touches tensor data.
 #include <mutex>
+#include <stdlib.h>
 #include <string.h>
 
 #include "../../include/leet_attn.h"
@@ -9,6 +10,8 @@
 namespace leet {
 hipError_t launch_fwd_bf16_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_bf16_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_bf16_coop_states(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
@@ -21,12 +24,26 @@ namespace {
 
 using leet::kChunk;
 
-// Sequences are cut into segments so that about this many workgroups exist (two
-// per compute unit of a 256-CU device), but no segment is shorter than kMinSegChunks
-// chunks: each extra segment costs one D x D fp32 state written, scanned and re-read.
-constexpr int kTargetWorkgroups = 512;
+// Sequences are cut into segments so that about this many workgroups exist, but no
+// segment is shorter than kMinSegChunks chunks: each extra segment costs one D x D fp32
+// state written, scanned and re-read, and every segment but the last has its K and V read
+// twice.  The wide kernels (one workgroup per segment) want two workgroups per compute
+// unit of a 256-CU device; the column-split bf16 kernel puts D/32 workgroups on a segment
+// and wants one per compute unit.
+constexpr int kTargetWorkgroupsWide = 512;
+constexpr int kTargetWorkgroupsCoop = 256;
 constexpr int kMinSegChunks = 8;
 constexpr int kMaxDevices = 64;
+
+// Kernel choice for bf16 prefill.  LEET_ATTN_BF16_KERNEL=wide|coop overrides (debug/measurement).
+bool use_coop_kernel() {
+    static const int choice = [] {
+        const char* e = getenv("LEET_ATTN_BF16_KERNEL");
+        if (e && strcmp(e, "wide") == 0) return 0;
+        return 1;
+    }();
+    return choice == 1;
+}
 
 struct Plan {
     int nseg;
@@ -34,13 +51,16 @@ struct Plan {
     size_t ws_bytes;
 };
 
-bool make_plan(long BH, int N, int D, int segments, Plan* plan) {
+bool make_plan(long BH, int N, int D, int dtype, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
+    const bool coop = dtype == LEET_BF16 && use_coop_kernel();
+    const long per_seg = coop ? BH * (D / 32) : BH;   // workgroups one segment of every sequence gives
+    const long target = coop ? kTargetWorkgroupsCoop : kTargetWorkgroupsWide;
     long want;
     if (segments > 0) {
         want = segments;
     } else {
-        want = (kTargetWorkgroups + BH - 1) / BH;
+        want = (target + per_seg - 1) / per_seg;
         long cap = nchunks / kMinSegChunks;
         if (cap < 1) cap = 1;
         if (want > cap) want = cap;
@@ -49,7 +69,7 @@ bool make_plan(long BH, int N, int D, int segments, Plan* plan) {
     if (want > nchunks) want = nchunks;
     const int seg_chunks = (int)((nchunks + want - 1) / want);
     const int nseg = (nchunks + seg_chunks - 1) / seg_chunks;
-    if (BH * (long)nseg >= (1L << 31)) return false;
+    if (per_seg * (long)nseg >= (1L << 28)) return false;
     plan->nseg = nseg;
     plan->seg_chunks = seg_chunks;
     plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * D * D * sizeof(float);
@@ -117,7 +137,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -151,14 +171,19 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
             }
         (void)hipEventRecord(ev[0], s);
     }
-    hipError_t e = bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s) : leet::launch_fwd_f32_states(p, (int)BH, d, s);
+    const bool coop = bf16 && use_coop_kernel();
+    hipError_t e = coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
+                   : bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s)
+                          : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     if (e == hipSuccess) {
         if (kernel_ms) (void)hipEventRecord(ev[1], s);
         e = leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
     }
     if (e == hipSuccess) {
         if (kernel_ms) (void)hipEventRecord(ev[2], s);
-        e = bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s) : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
+        e = coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
+            : bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s)
+                   : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
     }
     int rc = (e == hipSuccess) ? LEET_OK : LEET_ERR_LAUNCH;
     if (kernel_ms) {
@@ -203,7 +228,7 @@ size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segm
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(d, dtype, &status)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, d, dtype, segments, &plan)) return 0;
     return plan.ws_bytes;
 }
 

@@ -146,6 +146,19 @@ size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segm
  */
 int leet_attn_release_workspace(void);
 
+/*
+ * Tuning knob: which kernel a bf16 prefill uses.  Both compute the same chunked form (Alg. 2
+ * with the decaying mask) and pass the same parity tests; they differ in how the work is split.
+ *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns (default)
+ *   LEET_KERNEL_COLUMN_SPLIT  d/32 workgroups per (sequence, segment), 32 value columns each,
+ *                             placed on one XCD; fewer segments needed to fill the device
+ * Process-wide; takes effect for calls made after it returns.  Returns LEET_ERR_INVALID_ARG for
+ * any other value.
+ */
+typedef enum { LEET_KERNEL_WIDE = 0, LEET_KERNEL_COLUMN_SPLIT = 1 } leet_bf16_kernel;
+int leet_attn_set_bf16_kernel(int which);
+int leet_attn_get_bf16_kernel(void);
+
 /* Static, never-NULL description of a leet_status value. */
 const char *leet_attn_strerror(int status);
 

@@ -27,6 +27,8 @@ EXPORTED_SYMBOLS = (
     "leet_attn_forward_ex",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
+    "leet_attn_set_bf16_kernel",
+    "leet_attn_get_bf16_kernel",
     "leet_attn_workspace_bytes",
     "leet_attn_release_workspace",
     "leet_attn_strerror",
@@ -64,6 +66,10 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_workspace_bytes.restype = sz
     lib.leet_attn_release_workspace.argtypes = []
     lib.leet_attn_release_workspace.restype = i
+    lib.leet_attn_set_bf16_kernel.argtypes = [i]
+    lib.leet_attn_set_bf16_kernel.restype = i
+    lib.leet_attn_get_bf16_kernel.argtypes = []
+    lib.leet_attn_get_bf16_kernel.restype = i
     lib.leet_attn_strerror.argtypes = [i]
     lib.leet_attn_strerror.restype = ctypes.c_char_p
     lib.leet_attn_version.argtypes = []
@@ -112,6 +118,19 @@ def _stream_ptr(dev: torch.device) -> int:
 
 def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+KERNEL_WIDE, KERNEL_COLUMN_SPLIT = 0, 1
+
+
+def set_bf16_kernel(which: int) -> None:
+    st = lib.leet_attn_set_bf16_kernel(int(which))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_set_bf16_kernel")
+
+
+def get_bf16_kernel() -> int:
+    return int(lib.leet_attn_get_bf16_kernel())
 
 
 def workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0) -> int:

@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation, segment planning, workspace, launches.
 // Every step of the computation runs in the HIP kernels; nothing here touches tensor data.
+#include <atomic>
 #include <mutex>
 #include <stdlib.h>
 #include <string.h>
@@ -27,23 +28,17 @@ using leet::kChunk;
 // Sequences are cut into segments so that about this many workgroups exist, but no
 // segment is shorter than kMinSegChunks chunks: each extra segment costs one D x D fp32
 // state written, scanned and re-read, and every segment but the last has its K and V read
-// twice.  The wide kernels (one workgroup per segment) want two workgroups per compute
-// unit of a 256-CU device; the column-split bf16 kernel puts D/32 workgroups on a segment
-// and wants one per compute unit.
-constexpr int kTargetWorkgroupsWide = 512;
+// twice.  One workgroup per compute unit of a 256-CU device measured best for both kernel
+// families (the walk is HBM-bound from there on, and fewer segments mean less pre-pass and
+// scan traffic); the column-split bf16 kernel puts D/32 workgroups on a segment.
+constexpr int kTargetWorkgroupsWide = 256;
 constexpr int kTargetWorkgroupsCoop = 256;
 constexpr int kMinSegChunks = 8;
 constexpr int kMaxDevices = 64;
 
-// Kernel choice for bf16 prefill.  LEET_ATTN_BF16_KERNEL=wide|coop overrides (debug/measurement).
-bool use_coop_kernel() {
-    static const int choice = [] {
-        const char* e = getenv("LEET_ATTN_BF16_KERNEL");
-        if (e && strcmp(e, "wide") == 0) return 0;
-        return 1;
-    }();
-    return choice == 1;
-}
+// Kernel choice for bf16 prefill: LEET_KERNEL_WIDE (default) or LEET_KERNEL_COLUMN_SPLIT.
+std::atomic<int> g_bf16_kernel{LEET_KERNEL_WIDE};
+bool use_coop_kernel() { return g_bf16_kernel.load(std::memory_order_relaxed) == LEET_KERNEL_COLUMN_SPLIT; }
 
 struct Plan {
     int nseg;
@@ -280,6 +275,14 @@ const char* leet_attn_strerror(int status) {
     }
 }
 
-const char* leet_attn_version(void) { return "0.1.0"; }
+int leet_attn_set_bf16_kernel(int which) {
+    if (which != LEET_KERNEL_WIDE && which != LEET_KERNEL_COLUMN_SPLIT) return LEET_ERR_INVALID_ARG;
+    g_bf16_kernel.store(which, std::memory_order_relaxed);
+    return LEET_OK;
+}
+
+int leet_attn_get_bf16_kernel(void) { return g_bf16_kernel.load(std::memory_order_relaxed); }
+
+const char* leet_attn_version(void) { return "0.2.0"; }
 
 }  // extern "C"

@@ -1,4 +1,4 @@
-// Column-split chunk-walk kernel for bf16 inputs (gfx950, v_mfma_f32_16x16x32_bf16).
+// Column-split chunk-walk kernel for bf16 inputs (gfx950, v_mfma_f32_32x32x16_bf16).
 //
 // Same mathematics as the wide kernel in leet_fwd_bf16.hip -- Alg. 2 (Appendix B.2) with the
 // decaying mask of Eq. "BCMV" (Section 2.2) and the weight split of Alg. 4 (Appendix B.3):
@@ -9,30 +9,38 @@
 // but a different split of the work, made for few, long sequences.  Value columns are
 // independent of one another (O[:, c] and S[:, c] need only V[:, c]), so a sequence is
 // handled by D/32 workgroups, one per 32-column slice, on D/32 compute units; each reads
-// all of Q and K (the copies of one sequence are placed on one XCD so that three of the
-// four reads hit its L2) and its own 32 columns of V, and writes its 32 columns of O.
-// Inside a workgroup every product is cut into 16x16 tiles that are dealt out to the eight
-// waves (two per SIMD, so that one hides the LDS and MFMA latency of the other); what one
-// wave produces for the others goes through LDS in operand order:
+// all of Q and K (the copies of one sequence are placed on one XCD so that all but one of
+// the reads hit its L2) and its own 32 columns of V, and writes its 32 columns of O.
 //
-//   G1  P^T tile (jq, iq) = K[16jq..][:] Q[16iq..][:]^T, masked, -> LDS P[i][j] (bf16)
-//       ten tiles on and below the diagonal, one or two per wave
-//   G3  O^T tile (ch, iq) = S^T[16ch..][:] Q^T[:][16iq..]      wave w does ch = w%2, iq = w/2;
-//       S^T comes from LDS ST[c][dk] (bf16), written by the state owners after G4
-//   G2  O^T tile (ch, iq) += V^T[16ch..][keys] P^T[keys][16iq..]   V through transposing reads
-//   G4  S tile (dk block, ch) = gamma^L S + K^T (Gam V)         the (D/16) x 2 tiles dealt D/64 per wave
+// Inside a workgroup the waves are specialised, one 32x32 output tile per task, and hand
+// their products to one another through LDS in operand-register order:
 //
-// MFMA conventions (16x16x32): an A (B) operand holds, in lane l, row (column) l%16 and the
-// eight contraction slots 8(l/16)..8(l/16)+7; an accumulator holds, in lane l, column l%16
-// and rows 4(l/16)..4(l/16)+3.  Outputs are accumulated transposed (lane = token), so Lam is
-// one scalar per lane and a lane stores 16 contiguous bytes.
+//   waves 0..2   G1  score tile n: P^T = K rows x Q rows, decay mask, pack -> pfrag[n]
+//                    (tiles (jt,it) = (0,0), (1,1), (0,1)); after that G4 for state tile n
+//   waves 3, 4   G3  O^T[c][i] = S^T Q^T for row block it = w-3 (S^T from LDS st[c][dk]),
+//                    rows scaled by gamma^(i+1); then G2: O^T += V^T P^T (V through
+//                    transposing LDS reads, P from pfrag); store
+//   wave  5      G4  for state tile 3 (d = 128 only)
+//   waves 6, 7   staging only
+//   G4  S[dk tile][c] = gamma^L S + K^T (Gam V), A = K through transposing reads, B = the
+//       Gam-scaled V copy; the owner keeps its 32x32 fp32 tile in accumulators for the whole
+//       walk and publishes it as bf16 S^T[c][dk] for the G3 waves of the next chunk.
+//
+// MFMA conventions (32x32x16): an A (B) operand holds, in lane l, row (column) l%32 and the
+// eight contraction slots of group g = l/32; an accumulator holds, in lane l, column l%32
+// and, in register r, row m(r, g) = 8(r/4) + 4g + r%4.  A contraction may use any assignment
+// of indices to slots as long as A and B agree.  P^T accumulators (lane = query, registers =
+// keys) are a B operand as they are; the V fragments are read in the matching key order.  G4
+// assigns key-dimension index dk = 32t + pi(m) to accumulator row m (pi swaps bits 2 and 3 of
+// m), so registers 8h..8h+7 hold eight consecutive dk and S^T is published 16 bytes at a time.
+// Outputs are accumulated transposed (lane = token): Lam is one scalar per lane and a lane
+// stores 16 contiguous bytes.
 //
 // Q, K, the V slice and its Gam-scaled copy are double-buffered in LDS: chunk t+1 is written
-// from registers while chunk t is consumed and chunk t+2 is in flight from HBM, with two
-// workgroup barriers per chunk.  A ragged last chunk is right-aligned in the tile (rows
-// 64-L.. hold the tokens), which keeps every decay weight chunk-independent.
-#include <stdlib.h>
-
+// from registers while chunk t is consumed, and a ring of register stages keeps the loads of
+// three further chunks in flight; two workgroup barriers per chunk.  A ragged last chunk is
+// right-aligned in the tile (rows 64-L.. hold the tokens), which keeps every decay weight
+// chunk-independent.
 #include <type_traits>
 
 #include "leet_common.hpp"
@@ -45,13 +53,12 @@ template <int D>
 struct CoopSmem {
     static constexpr int RSQ = D + 8;   // Q, K row stride (elements): 16-byte row reads spread over the banks
     static constexpr int RSV = 48;      // V slice: 32 columns + pad; 4 rows x 32 B of a transposing read stay apart
-    static constexpr int RSP = 72;      // P[i][j]: 64 keys + pad
     static constexpr int RST = D + 8;   // S^T[c][dk]
     uint16_t q[2][kChunk * RSQ];
     uint16_t k[2][kChunk * RSQ];
     uint16_t v[2][kChunk * RSV];
     uint16_t vs[2][kChunk * RSV];       // Gam V: row j scaled by gamma^(63-j)
-    uint16_t p[kChunk * RSP];
+    u32x4 pfrag[3][2][64];              // masked P^T tiles as B operands: [tile][register half][lane]
     uint16_t st[32 * RST];
     float pw[kChunk + 4];               // gamma^n, n = 0..64
 };
@@ -70,36 +77,31 @@ __device__ __forceinline__ u32x2 lds_tr(const uint16_t* p) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-// eight consecutive keys (two transposing reads, four rows apart) of this lane's column
+// keys {k0..k0+3} and {k0+8..k0+11} of this lane's column: the order in which a 32x32
+// accumulator holds its rows (k0 = 16 f + 4 g)
 __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* p, int row_stride) {
-    u32x2 a = lds_tr(p), b = lds_tr(p + 4 * row_stride);
+    u32x2 a = lds_tr(p), b = lds_tr(p + 8 * row_stride);
     u32x4 r = {a.x, a.y, b.x, b.y};
     return __builtin_bit_cast(bf16x8, r);
 }
 
-__device__ __forceinline__ u32x2 pack4(const f32x4& x) {
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-    bf16x4 r;
+// registers 8h .. 8h+7 of an accumulator tile -> bf16 operand
+__device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int h) {
+    bf16x8 r;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = (__bf16)x[e];
-    return __builtin_bit_cast(u32x2, r);
+    for (int e = 0; e < 8; ++e) r[e] = (__bf16)acc[8 * h + e];
+    return r;
 }
 
-__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// One score tile: P^T[16JQ.., 16IQ..] = K rows x Q rows, masked by gamma^(i-j), to LDS P[i][j].
-template <int D, int JQ, int IQ>
-__device__ __forceinline__ void score_tile(const uint16_t* k_row, const uint16_t* q_row, uint16_t* p_wr,
-                                           const f32x4 (&wgt)[4]) {
-    constexpr int RSQ = CoopSmem<D>::RSQ, RSP = CoopSmem<D>::RSP;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s)
-        acc = mfma16(frag16(k_row + 16 * JQ * RSQ + 32 * s), frag16(q_row + 16 * IQ * RSQ + 32 * s), acc);
-    acc *= wgt[IQ - JQ];
-    *reinterpret_cast<u32x2*>(p_wr + 16 * IQ * RSP + 16 * JQ) = pack4(acc);
+    for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+    return z;
 }
 
 }  // namespace coop
@@ -110,12 +112,11 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     using namespace coop;
     constexpr int NT = 512;       // threads: eight waves
     constexpr int SL = D / 32;    // column slices (workgroups) per sequence segment
-    constexpr int NS = D / 32;    // contraction steps over the key dimension
-    constexpr int TPW = D / 64;   // state tiles (16 key rows x 16 columns) per wave
+    constexpr int DT = D / 32;    // 32-row state tiles of the slice
     constexpr int PR = D / 8;     // 16-byte pieces per Q/K row
     constexpr int QPT = D / 64;   // Q (and K) pieces per thread per chunk
     constexpr int RPP = NT / PR;  // rows covered by one piece index
-    constexpr int RSQ = CoopSmem<D>::RSQ, RSV = CoopSmem<D>::RSV, RSP = CoopSmem<D>::RSP, RST = CoopSmem<D>::RST;
+    constexpr int RSQ = CoopSmem<D>::RSQ, RSV = CoopSmem<D>::RSV, RST = CoopSmem<D>::RST;
     __shared__ __attribute__((aligned(16))) CoopSmem<D> sm;
 
     // Block -> (sequence segment, column slice).  Consecutive block ids go round-robin over
@@ -130,9 +131,16 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     const int h = bh % p.H;
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63, r16 = l & 15, q4 = l >> 4;
+    const int w = tid >> 6, l = tid & 63, ln = l & 31, g = l >> 5;
+    const int s16 = l & 15, half = (l >> 4) & 1;
     const int c0 = 32 * slice;
-    const int o_ch = w & 1, o_iq = w >> 1;  // the output tile of this wave
+
+    // ---- roles
+    const bool score_wave = kOut && w < 3;                       // G1 tile n = w
+    const bool out_wave = kOut && (w == 3 || w == 4);            // output row block it = w - 3
+    const int st_tile = (w < 3) ? w : (w == 5 ? 3 : -1);         // state tile owned (G4), if it exists
+    const bool state_wave = st_tile >= 0 && st_tile < DT;
+    const int it_own = w - 3;
 
     const int tok_begin = seg * p.seg_chunks * kChunk;
     const int tok_end = (seg == p.nseg - 1) ? p.N : tok_begin + p.seg_chunks * kChunk;
@@ -147,44 +155,32 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     {
         const double gd = (double)p.gamma[h];
         for (int n = tid; n <= kChunk; n += NT) sm.pw[n] = (float)pow_int(gd, n);
-        if (kOut) {  // P above the diagonal is read by G2 as part of 32-key steps and must stay zero
-            u32x4 z = {0u, 0u, 0u, 0u};
-            for (int n = tid; n < kChunk * RSP / 8; n += NT) reinterpret_cast<u32x4*>(sm.p)[n] = z;
-        }
     }
 
-    // ---- state tiles of this wave: tile k covers key rows 16 dkb(k) .. +15 and columns 16 ch(k) .. +15
-    // of the slice; S[k][r] = S[dk = 16 dkb + 4 q4 + r][c = c0 + 16 ch + r16].
-    auto tile_dkb = [&](int k) { return (w * TPW + k) >> 1; };
-    auto tile_ch = [&](int k) { return (w * TPW + k) & 1; };
-    f32x4 S[TPW];
-    {
+    // ---- state tile of this wave: S[r] = S[dk = 32 t + pi(m(r, g))][c = c0 + ln]
+    auto dk_of = [&](int r) {
+        // m = 8(r/4) + 4g + r%4 ; pi swaps the 4- and 8-bits: dk = 16(r/8) + 8g + 4((r/4)&1) + r%4
+        return 32 * st_tile + 16 * (r >> 3) + 8 * g + 4 * ((r >> 2) & 1) + (r & 3);
+    };
+    f32x16 S = zero16();
+    if (state_wave) {
         const float* src = nullptr;
         if (kOut) {
             if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
             else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * D;
         }
+        if (src) {
 #pragma unroll
-        for (int k = 0; k < TPW; ++k)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                int dk = 16 * tile_dkb(k) + 4 * q4 + r;
-                S[k][r] = src ? src[dk * D + c0 + 16 * tile_ch(k) + r16] : 0.0f;
-            }
+            for (int r = 0; r < 16; ++r) S[r] = src[dk_of(r) * D + c0 + ln];
+        }
     }
-    // S^T[c][dk] in LDS, 4 consecutive dk per lane and tile
-    int st_wr_off[TPW], k_tr_off[TPW], vs_tr_off[TPW];
-#pragma unroll
-    for (int k = 0; k < TPW; ++k) {
-        st_wr_off[k] = (16 * tile_ch(k) + r16) * RST + 16 * tile_dkb(k) + 4 * q4;
-        k_tr_off[k] = (8 * q4 + (r16 >> 2)) * RSQ + 16 * tile_dkb(k) + 4 * (r16 & 3);
-        vs_tr_off[k] = (8 * q4 + (r16 >> 2)) * RSV + 16 * tile_ch(k) + 4 * (r16 & 3);
-    }
+    // S^T[c][dk] in LDS: registers 8h..8h+7 are dk = 32 t + 16 h + 8 g + (0..7)
+    u32x4* st_wr = reinterpret_cast<u32x4*>(&sm.st[ln * RST + 32 * max(st_tile, 0) + 8 * g]);  // + 2h (16 elements)
     auto publish_state = [&]() {
-#pragma unroll
-        for (int k = 0; k < TPW; ++k) *reinterpret_cast<u32x2*>(&sm.st[st_wr_off[k]]) = pack4(S[k]);
+        st_wr[0] = __builtin_bit_cast(u32x4, pack_half(S, 0));
+        st_wr[2] = __builtin_bit_cast(u32x4, pack_half(S, 1));
     };
-    if (kOut) publish_state();
+    if (kOut && state_wave) publish_state();
 
     // ---- staging: thread -> pieces.  Q, K: QPT pieces of 16 bytes; V slice: one piece, fetched
     // by both halves of the workgroup (so that every thread issues the same loads) and written
@@ -220,7 +216,7 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
         st.v = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row, shift) * D + c0 + v_cc * 8));
     };
 
-    __syncthreads();  // tables, zeroed P, S^T visible
+    __syncthreads();  // tables, S^T visible
 
     const float v_scale = sm.pw[kChunk - 1 - v_row];  // gamma^(63-j) for this thread's V row
     auto store_tiles = [&](Stage& st, int buf, int tok0) {
@@ -256,23 +252,23 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     };
 
     // ---- per-lane constants
-    f32x4 wgt[4];  // wgt[diff][r] = gamma^(16 diff + r16 - 4 q4 - r), zero above the diagonal
-    if (kOut) {
+    // decay weights of the score tile this wave produces: i - j = 32 (it - jt) + ln - jr
+    f32x16 wgt = zero16();
+    if (score_wave) {
 #pragma unroll
-        for (int diff = 0; diff < 4; ++diff)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                int n = 16 * diff + r16 - 4 * q4 - r;
-                wgt[diff][r] = (n >= 0) ? sm.pw[max(n, 0)] : 0.0f;
-            }
+        for (int r = 0; r < 16; ++r) {
+            int n = ln - (8 * (r >> 2) + 4 * g + (r & 3));
+            float diag = (n >= 0) ? sm.pw[max(n, 0)] : 0.0f;
+            wgt[r] = (w == 2) ? sm.pw[32 + n] : diag;
+        }
     }
-    const float lam_full = sm.pw[16 * o_iq + r16 + 1];  // gamma^(i+1) in a full chunk
-    const float gl_full = sm.pw[kChunk];                // gamma^64
-    const int row_off = r16 * RSQ + 8 * q4;             // 16-byte row fragments of Q, K
-    const int tr_off_v = (8 * q4 + (r16 >> 2)) * RSV + 16 * o_ch + 4 * (r16 & 3);
-    const uint16_t* st_rd = &sm.st[(16 * o_ch + r16) * RST + 8 * q4];  // + 32 s
-    const uint16_t* p_rd = &sm.p[(16 * o_iq + r16) * RSP + 8 * q4];    // + 32 u
-    uint16_t* p_wr = &sm.p[r16 * RSP + 4 * q4];                        // + 16 IQ RSP + 16 JQ
+    const float lam_full = sm.pw[min(32 * max(it_own, 0) + ln + 1, kChunk)];  // gamma^(i+1) in a full chunk
+    const float gl_full = sm.pw[kChunk];                                       // gamma^64
+    const int row_off = ln * RSQ + 8 * g;  // 16-byte row fragments of Q, K: + 32 tile RSQ + 16 s
+    // transposing reads: lane supplies row 4g + s16/4 (+ 16 f, + 8 for the second half) and four columns
+    const int tr_off_v = (4 * g + (s16 >> 2)) * RSV + 16 * half + 4 * (s16 & 3);
+    const int tr_off_k = (4 * g + (s16 >> 2)) * RSQ + 32 * max(st_tile, 0) + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);
+    const uint16_t* st_rd = &sm.st[ln * RST + 8 * g];  // + 16 s
 
     // ---- the work of one chunk.  kRagged = false: a full chunk inside the steady-state loop,
     // where every global load and store is issued unconditionally, so that the wait for the
@@ -296,56 +292,81 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
         const uint16_t* q_row = &sm.q[buf][row_off];
         const uint16_t* k_row = &sm.k[buf][row_off];
 
-        f32x4 o;
-        if (kOut) {
-            // G1: ten score tiles (jq <= iq) dealt over the waves
-            switch (w) {
-                case 0: score_tile<D, 0, 0>(k_row, q_row, p_wr, wgt); score_tile<D, 0, 3>(k_row, q_row, p_wr, wgt); break;
-                case 1: score_tile<D, 1, 1>(k_row, q_row, p_wr, wgt); score_tile<D, 1, 3>(k_row, q_row, p_wr, wgt); break;
-                case 2: score_tile<D, 0, 1>(k_row, q_row, p_wr, wgt); break;
-                case 3: score_tile<D, 2, 2>(k_row, q_row, p_wr, wgt); break;
-                case 4: score_tile<D, 0, 2>(k_row, q_row, p_wr, wgt); break;
-                case 5: score_tile<D, 1, 2>(k_row, q_row, p_wr, wgt); break;
-                case 6: score_tile<D, 2, 3>(k_row, q_row, p_wr, wgt); break;
-                default: score_tile<D, 3, 3>(k_row, q_row, p_wr, wgt); break;
-            }
-
-            // G3: O^T tile (o_ch, o_iq) = S^T Q^T, scaled by gamma^(i+1)
-            const uint16_t* q_own = q_row + 16 * o_iq * RSQ;
-            o = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < NS; ++s) o = mfma16(frag16(st_rd + 32 * s), frag16(q_own + 32 * s), o);
-            o *= kRagged ? sm.pw[max(16 * o_iq + r16 + 1 - shift, 0)] : lam_full;
-
-            __syncthreads();  // P visible; every wave is done reading S^T
-
-            // G2: O^T += V^T P^T over the keys up to this row block, 32 keys per step
-            const uint16_t* v_tr = &sm.v[buf][tr_off_v];
-            const int nu = (o_iq >> 1) + 1;
-            for (int u = 0; u < nu; ++u) o = mfma16(frag_tr(v_tr + 32 * u * RSV, RSV), frag16(p_rd + 32 * u), o);
-
-            // store: lane = token 16 o_iq + r16, registers = columns c0 + 16 o_ch + 4 q4 + (0..3)
-            const int i = 16 * o_iq + r16;
-            if (!kRagged || i >= shift) {
-                float* oc = og + (size_t)(tok0 - shift) * D;  // wave-uniform
-                *reinterpret_cast<f32x4*>(oc + (unsigned)(i * D + c0 + 16 * o_ch + 4 * q4)) = o;
-            }
-        }
-
-        // G4: S = gamma^L S + K^T (Gam V) for this wave's state tiles
-        {
+        // G4 math: S = gamma^L S + K^T (Gam V) for the tile this wave owns
+        auto state_update = [&]() {
             const float gl = kRagged ? sm.pw[Lc] : gl_full;
 #pragma unroll
-            for (int k = 0; k < TPW; ++k) S[k] *= gl;
+            for (int r = 0; r < 16; ++r) S[r] *= gl;
+            const uint16_t* k_tr = &sm.k[buf][tr_off_k];
+            const uint16_t* vs_tr = &sm.vs[buf][tr_off_v];
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                // with two tiles per wave both share the key rows (dkb) and differ in the column half
-                const bf16x8 ka = frag_tr(&sm.k[buf][k_tr_off[0]] + 32 * u * RSQ, RSQ);
+            for (int f = 0; f < 4; ++f)
+                S = mfma32(frag_tr(k_tr + 16 * f * RSQ, RSQ), frag_tr(vs_tr + 16 * f * RSV, RSV), S);
+        };
+
+        if (kOut) {
+            f32x16 o = zero16();
+            if (score_wave) {
+                // G1: score tile n = w, (jt, it) = (0,0), (1,1), (0,1)
+                const int jt = (w == 1) ? 1 : 0, it = (w == 0) ? 0 : 1;
+                const uint16_t* ka = k_row + 32 * jt * RSQ;
+                const uint16_t* qa = q_row + 32 * it * RSQ;
+                f32x16 acc = zero16();
 #pragma unroll
-                for (int k = 0; k < TPW; ++k)
-                    S[k] = mfma16(ka, frag_tr(&sm.vs[buf][vs_tr_off[k]] + 32 * u * RSV, RSV), S[k]);
+                for (int s = 0; s < D / 16; ++s) acc = mfma32(frag16(ka + 16 * s), frag16(qa + 16 * s), acc);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
+                sm.pfrag[w][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
+                sm.pfrag[w][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
+            } else if (out_wave) {
+                // G3: O^T = S^T Q^T for row block it_own, rows scaled by gamma^(i+1)
+                const uint16_t* qa = q_row + 32 * it_own * RSQ;
+#pragma unroll
+                for (int s = 0; s < D / 16; ++s) o = mfma32(frag16(st_rd + 16 * s), frag16(qa + 16 * s), o);
+                const float lam = kRagged ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[r] *= lam;
+            } else if (state_wave) {
+                state_update();
             }
-            if (kOut) publish_state();
+
+            __syncthreads();  // P visible; the output waves are done reading S^T
+
+            if (score_wave) {
+                if (state_wave) {
+                    state_update();
+                    publish_state();
+                }
+            } else if (out_wave) {
+                // G2: O^T += V^T P^T over the score tiles of this row block
+                const uint16_t* v_tr = &sm.v[buf][tr_off_v];
+                if (it_own == 0) {
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh)
+                        o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[0][hh][l]), o);
+                } else {
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[2][hh][l]), o);
+                        o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[1][hh][l]), o);
+                    }
+                }
+                // store: lane = token 32 it + ln, registers 4q..4q+3 = columns c0 + 8q + 4g + (0..3)
+                const int i = 32 * it_own + ln;
+                if (!kRagged || i >= shift) {
+                    float* oc = og + (size_t)(tok0 - shift) * D;  // wave-uniform
+                    const unsigned ooff = (unsigned)(i * D + c0 + 4 * g);
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
+                        *reinterpret_cast<f32x4*>(oc + ooff + 8 * qd) = val;
+                    }
+                }
+            } else if (state_wave) {
+                publish_state();
+            }
+        } else {
+            if (state_wave) state_update();
         }
         __syncthreads();  // chunk t+1 tiles and S^T visible; P and this chunk's tiles free
     };
@@ -375,16 +396,15 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     } else {
         dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * D;
     }
-    if (dst) {
+    if (dst && state_wave) {
 #pragma unroll
-        for (int k = 0; k < TPW; ++k)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                int dk = 16 * tile_dkb(k) + 4 * q4 + r;
-                dst[dk * D + c0 + 16 * tile_ch(k) + r16] = S[k][r];
-            }
+        for (int r = 0; r < 16; ++r) dst[dk_of(r) * D + c0 + ln] = S[r];
     }
 }
+
+// Measurement switch: number the slices of a segment consecutively (spreading them over the
+// XCDs) instead of placing them on one XCD.  Off by default.
+bool g_coop_consecutive_ids = false;
 
 namespace {
 template <int D, bool kOut>
@@ -392,7 +412,7 @@ hipError_t launch_coop(const FwdParams& p, int BH, hipStream_t stream) {
     const int ngroups = BH * (kOut ? p.nseg : p.nseg - 1);
     if (ngroups <= 0) return hipSuccess;
     const int blocks = 8 * (D / 32) * ((ngroups + 7) / 8);
-    static const int map_mode = [] { const char* e = getenv("LEET_ATTN_COOP_MAP"); return e ? atoi(e) : 0; }();
+    const int map_mode = g_coop_consecutive_ids ? 1 : 0;
     hipLaunchKernelGGL((fwd_bf16_coop_kernel<D, kOut>), dim3(blocks), dim3(512), 0, stream, p, ngroups, map_mode);
     return hipGetLastError();
 }

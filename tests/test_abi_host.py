@@ -88,6 +88,20 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert ex(p, p, p, p, p, odd, None, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
 
 
+def test_kernel_choice_setter(lib):
+    from paper_2501_02573_amd import binding as b
+    assert b.get_bf16_kernel() == b.KERNEL_WIDE
+    b.set_bf16_kernel(b.KERNEL_COLUMN_SPLIT)
+    assert b.get_bf16_kernel() == b.KERNEL_COLUMN_SPLIT
+    # the column-split kernel needs fewer segments for the same number of workgroups
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 0
+    b.set_bf16_kernel(b.KERNEL_WIDE)
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 4 * 16 * 3 * 128 * 128 * 4
+    with pytest.raises(b.LeetAttnError):
+        b.set_bf16_kernel(7)
+    assert b.get_bf16_kernel() == b.KERNEL_WIDE
+
+
 def test_binding_rejects_cpu_tensors(lib):
     import torch
     from paper_2501_02573_amd import binding as b

@@ -244,3 +244,46 @@ def test_errors_write_nothing(B):
     assert ei.value.status == B.LEET_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert torch.all(out == 7.0)
+
+
+# ---------------------------------------------------------------- the column-split bf16 kernel
+@pytest.fixture
+def column_split(B):
+    B.set_bf16_kernel(B.KERNEL_COLUMN_SPLIT)
+    yield B
+    B.set_bf16_kernel(B.KERNEL_WIDE)
+
+
+COOP_SHAPES = [
+    (1, 1, 1, 128, 0), (2, 1, 64, 64, 0), (1, 3, 200, 128, 0), (2, 3, 777, 64, 3), (1, 4, 777, 128, 4),
+    (3, 5, 1536, 128, 0), (1, 9, 1000, 128, 2), (1, 1, 4096, 128, 16),
+]
+
+
+@pytest.mark.parametrize("shape", COOP_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_seg%d" % s)
+def test_column_split_kernel_shapes(column_split, shape):
+    """Same oracle, same tolerances, for the kernel that gives each 32-column slice its own workgroup."""
+    B = column_split
+    Bn, H, N, d, segs = shape
+    say(f"case column-split shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=2000 + N + d, gamma=gamma)
+    rng = np.random.default_rng(N + 1)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.1).astype(np.float32))
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    s_out = torch.empty_like(ds_in)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    out = B.leet_attn_forward_ex(dq, dk, dv, dg, state_in=ds_in, state_out=s_out, segments=segs).cpu().numpy()
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+    check(out, ref, "bf16", "out")
+    check(s_out.cpu().numpy(), s_ref, "bf16", "final state")
+
+
+def test_column_split_kernel_headline_config(column_split):
+    B = column_split
+    cfg = W.CONFIG3
+    say(f"case column-split {cfg}")
+    q, k, v, gamma = W.make_forward_inputs(cfg)
+    out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out, ref, cfg.dtype, "vs recurrent (all elements)")

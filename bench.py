@@ -2,16 +2,18 @@
 """Benchmark of the MI355X decayed causal linear attention library (one GPU).
 
 A step is one pass of the whole prefill hot path -- stage, scores, mask, intra and inter
-outputs, store, state update -- over one batch of the headline workload:
-B=4, H=16, N=4096, d=128, bf16 inputs, fp32 accumulate and output, per-head
-gamma_h = 1 - 2^-(5 + 3h/15), seeded synthetic q, k, v ~ N(0,1)/sqrt(d).  Inputs are
-resident in HBM before the timed region.  The decode step (config 5) and the
+outputs, store, state update (segment pre-pass, segment scan and chunk walk) -- over one batch
+of the headline workload: B=4, H=16, N=4096, d=128, bf16 inputs, fp32 accumulate and output,
+per-head gamma_h = 1 - 2^-(5 + 3h/15), seeded synthetic q, k, v ~ N(0,1)/sqrt(d).  Inputs
+are resident in HBM before the timed region.  The decode step (config 5) and the
 long-context prefill (config 4) are timed in the same run and reported under "extra".
 
-Prints ONE JSON line.  ``value`` is tokens/s (B*N per step) of the headline workload.
-``roofline`` is for the dominant kernel (the chunk walk), whose per-launch duration is
-measured with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle
-(recurrent form) timed on this host's cores on the same workload.
+Prints ONE JSON line.  ``value`` is tokens/s (B*N per step) of the headline workload over
+exactly --steps steps of plain library calls; ``ms_per_step_graph`` is the same step captured
+once into a HIP graph and replayed (reported for comparison, it measured no faster).
+``roofline`` is for the dominant kernel (the chunk walk), whose per-launch duration is measured
+with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle (recurrent form)
+timed on this host's cores on the same workload.
 """
 from __future__ import annotations
 
@@ -25,7 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
@@ -36,7 +38,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
+    ap.add_argument("--no-graph", action="store_true", help="time plain calls only (no HIP graph replay)")
     ap.add_argument("--segments", type=int, default=0, help="0 = library's choice (the shipped configuration)")
+    ap.add_argument("--kernel", choices=["wide", "column-split"], default="wide",
+                    help="bf16 prefill kernel (wide is the library default)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain 1 GiB copy kernel once (known traffic, for scaling profiler byte counters)")
     return ap.parse_args()
@@ -52,15 +57,41 @@ def alg_flops_forward(cfg):
     return cfg.B * cfg.H * cfg.N * (4 * cfg.d * cfg.d + 2 * 64 * cfg.d)
 
 
-def time_forward(binding, torch, q, k, v, gamma, out, steps, warmup, segments):
+def time_eager(torch, step, steps, warmup):
     for _ in range(warmup):
-        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+        step()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_graph(torch, step, steps, warmup):
+    """One step captured into a HIP graph, replayed `steps` times; None if capture fails."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+    except Exception as exc:  # noqa: BLE001  (fall back to the eager figure, say why)
+        print(f"bench.py: HIP graph capture unavailable ({exc}); reporting eager timing", file=sys.stderr)
+        return None
 
 
 def kernel_times(binding, q, k, v, gamma, out, reps, segments):
@@ -71,16 +102,30 @@ def kernel_times(binding, q, k, v, gamma, out, reps, segments):
     return [a / reps for a in acc]
 
 
-def load_traffic(workload):
+def load_traffic(workload, kernel):
     """HBM bytes per launch of the dominant kernel from the committed profiler summary, or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             rec = json.load(f)
-        ent = rec.get(workload)
+        ent = rec.get(f"{workload}/{kernel}")
         return None if ent is None else ent.get("hbm_bytes_per_launch")
     except (OSError, ValueError):
         return None
+
+
+def prefill_leg(torch, binding, W, cfg, dev, steps, warmup, segments, use_graph):
+    q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
+    out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
+
+    def step():
+        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+
+    ms_eager = time_eager(torch, step, steps, warmup)
+    ms_graph = time_graph(torch, step, steps, warmup) if use_graph else None
+    kms = kernel_times(binding, q, k, v, gamma, out, max(3, min(steps, 20)), segments)
+    del q, k, v, out
+    return ms_eager, ms_graph, kms
 
 
 def main():
@@ -98,13 +143,14 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    binding.set_bf16_kernel(binding.KERNEL_COLUMN_SPLIT if args.kernel == "column-split" else binding.KERNEL_WIDE)
+    walk_name = {"wide": "fwd_bf16_kernel<128,true>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[args.kernel]
 
     # ---------------- headline: config 3
     cfg = W.CONFIG3
-    q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
-    out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
-    ms = time_forward(binding, torch, q, k, v, gamma, out, args.steps, args.warmup, args.segments)
-    kms = kernel_times(binding, q, k, v, gamma, out, max(5, min(args.steps, 50)), args.segments)
+    ms_eager, ms_graph, kms = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup, args.segments,
+                                          not args.no_graph)
+    ms = ms_eager
     tokens = cfg.B * cfg.N
     nbytes = alg_bytes_forward(cfg, 2)
     nflops = alg_flops_forward(cfg)
@@ -123,25 +169,26 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "N": cfg.N, "d": cfg.d,
-                   "chunk": 64, "segments": args.segments or "auto", "gamma": "1-2^-(5+3h/15)",
-                   "seed": cfg.seed, "out_dtype": "f32"},
+                   "chunk": 64, "segments": args.segments or "auto", "kernel": args.kernel,
+                   "launch": "eager",
+                   "gamma": "1-2^-(5+3h/15)", "seed": cfg.seed, "out_dtype": "f32"},
+        "ms_per_step_graph": ms_graph,
         "tflops_algorithmic": nflops / (ms * 1e-3) / 1e12,
         "mfma_peak_frac": nflops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "hbm_frac_whole_step": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": {"segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": kms[2]},
         "roofline": {
-            "kernel": "fwd_bf16_kernel<128,true> (chunk walk)",
+            "kernel": f"{walk_name} (chunk walk)",
             "bound": "hbm",
             "achieved": nbytes / (walk_ms * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": nbytes / (walk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": load_traffic(cfg.name),
+            "traffic": load_traffic(cfg.name, args.kernel),
             "algorithmic_bytes_per_launch": nbytes,
             "avg_launch_ms": walk_ms,
         },
     }
-    del q, k, v, out
 
     if args.calibrate:
         nb = 1 << 30
@@ -155,19 +202,18 @@ def main():
     if not args.no_extra:
         extra = {}
         cfg4 = W.CONFIG4
-        q, k, v, gamma4 = (t.to(dev) for t in W.make_forward_inputs(cfg4))
-        out = torch.empty((cfg4.B, cfg4.H, cfg4.N, cfg4.d), dtype=torch.float32, device=dev)
-        ms4 = time_forward(binding, torch, q, k, v, gamma4, out, max(5, args.steps // 2), max(2, args.warmup // 2), 0)
-        kms4 = kernel_times(binding, q, k, v, gamma4, out, 10, 0)
+        e4, g4, kms4 = prefill_leg(torch, binding, W, cfg4, dev, max(5, args.steps // 2), max(2, args.warmup // 2), 0,
+                                   not args.no_graph)
+        ms4 = e4
         b4, f4 = alg_bytes_forward(cfg4, 2), alg_flops_forward(cfg4)
         extra["long_context"] = {
-            "workload": cfg4.name, "ms_per_step": ms4, "tokens_per_s": cfg4.B * cfg4.N / (ms4 * 1e-3),
+            "workload": cfg4.name, "ms_per_step": ms4, "ms_per_step_graph": g4,
+            "tokens_per_s": cfg4.B * cfg4.N / (ms4 * 1e-3),
             "tflops_algorithmic": f4 / (ms4 * 1e-3) / 1e12,
             "hbm_frac_whole_step": b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "kernel_ms": {"segment_state_prepass": kms4[0], "segment_scan": kms4[1], "chunk_walk": kms4[2]},
             "walk_hbm_frac": b4 / (kms4[2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
-        del q, k, v, out
 
         c5 = W.CONFIG5
         state0, gamma5, steps_it = W.decode_stream(c5)
@@ -191,9 +237,10 @@ def main():
             "workload": c5.name, "us_per_step": ms5 * 1e3, "tokens_per_s": c5.B / (ms5 * 1e-3),
             "roofline": {"kernel": "decode_kernel<128,true>", "bound": "hbm",
                          "achieved": b5 / (ms5 * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": load_traffic(c5.name, "decode"),
                          "algorithmic_bytes_per_launch": b5,
-                         "note": "the 128 MiB state fits the 256 MB Infinity Cache"},
+                         "note": "256 back-to-back steps; the 128 MiB state fits the 256 MB Infinity Cache"},
         }
         result["extra"] = extra
         del S, qkv, o

@@ -106,9 +106,11 @@ int leet_attn_forward_ex(const void *q, const void *k, const void *v, const floa
                          int B, int H, int N, int d, int dtype, void *stream);
 
 /*
- * Measurement aid: exactly leet_attn_forward_ex, but HIP events are recorded on `stream`
- * around each of the three kernels a prefill launches and the call waits for them.
- *   kernel_ms  HOST pointer to 3 floats, filled with the milliseconds of
+ * Measurement aid: computes what leet_attn_forward_ex computes, with HIP events recorded on
+ * `stream` around each of the three kernels a prefill launches; the call waits for them.
+ * The pre-pass and the walk (which write the same values each time) are launched five times
+ * back to back between their events and the time is divided by five; the scan runs once.
+ *   kernel_ms  HOST pointer to 3 floats, filled with the milliseconds per launch of
  *              [0] the segment-state pre-pass, [1] the segment scan, [2] the chunk walk
  *              ([0] and [1] are 0 when the plan has a single segment).
  * Synchronous (returns after the work has finished); not for use under graph capture.

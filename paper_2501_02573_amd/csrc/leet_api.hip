@@ -156,41 +156,59 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = dtype == LEET_BF16;
 
-    // Optional per-kernel timing: HIP events on the launch stream between the three launches.
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    if (kernel_ms) {
-        for (int i = 0; i < 4; ++i)
-            if (hipEventCreate(&ev[i]) != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
-                return LEET_ERR_LAUNCH;
-            }
-        (void)hipEventRecord(ev[0], s);
-    }
     const bool coop = bf16 && use_coop_kernel();
-    hipError_t e = coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
-                   : bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s)
-                          : leet::launch_fwd_f32_states(p, (int)BH, d, s);
-    if (e == hipSuccess) {
-        if (kernel_ms) (void)hipEventRecord(ev[1], s);
-        e = leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
+    auto launch_states = [&]() {
+        return coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
+               : bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s)
+                      : leet::launch_fwd_f32_states(p, (int)BH, d, s);
+    };
+    auto launch_scan = [&]() {
+        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
+    };
+    auto launch_walk = [&]() {
+        return coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
+               : bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s)
+                      : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
+    };
+
+    if (!kernel_ms) {
+        hipError_t e = launch_states();
+        if (e == hipSuccess) e = launch_scan();
+        if (e == hipSuccess) e = launch_walk();
+        return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
     }
-    if (e == hipSuccess) {
-        if (kernel_ms) (void)hipEventRecord(ev[2], s);
-        e = coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
-            : bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s)
-                   : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
-    }
-    int rc = (e == hipSuccess) ? LEET_OK : LEET_ERR_LAUNCH;
-    if (kernel_ms) {
-        if (rc == LEET_OK) {
-            (void)hipEventRecord(ev[3], s);
-            if (hipEventSynchronize(ev[3]) != hipSuccess) rc = LEET_ERR_LAUNCH;
-            for (int i = 0; i < 3 && rc == LEET_OK; ++i)
-                if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) rc = LEET_ERR_LAUNCH;
-            if (plan.nseg <= 1) kernel_ms[0] = kernel_ms[1] = 0.0f;  // nothing was launched in those slots
+
+    // Per-kernel timing: HIP events on the launch stream around each kernel.  The pre-pass and
+    // the walk write the same values every time they run, so each is launched kProfileRepeat
+    // times back to back between its two events and the time divided, which takes the event and
+    // launch overhead out of the figure; the scan rewrites its input in place and runs once.
+    constexpr int kProfileRepeat = 5;
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    for (int i = 0; i < 6; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+            return LEET_ERR_LAUNCH;
         }
-        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(ev[i]);
+    hipError_t e = hipSuccess;
+    (void)hipEventRecord(ev[0], s);
+    for (int r = 0; r < kProfileRepeat && e == hipSuccess; ++r) e = launch_states();
+    (void)hipEventRecord(ev[1], s);
+    (void)hipEventRecord(ev[2], s);
+    if (e == hipSuccess) e = launch_scan();
+    (void)hipEventRecord(ev[3], s);
+    (void)hipEventRecord(ev[4], s);
+    for (int r = 0; r < kProfileRepeat && e == hipSuccess; ++r) e = launch_walk();
+    (void)hipEventRecord(ev[5], s);
+    int rc = (e == hipSuccess) ? LEET_OK : LEET_ERR_LAUNCH;
+    if (hipEventSynchronize(ev[5]) != hipSuccess) rc = LEET_ERR_LAUNCH;
+    for (int i = 0; i < 3 && rc == LEET_OK; ++i)
+        if (hipEventElapsedTime(&kernel_ms[i], ev[2 * i], ev[2 * i + 1]) != hipSuccess) rc = LEET_ERR_LAUNCH;
+    if (rc == LEET_OK) {
+        kernel_ms[0] /= kProfileRepeat;
+        kernel_ms[2] /= kProfileRepeat;
+        if (plan.nseg <= 1) kernel_ms[0] = kernel_ms[1] = 0.0f;  // nothing was launched in those slots
     }
+    for (int i = 0; i < 6; ++i) (void)hipEventDestroy(ev[i]);
     return rc;
 }
 

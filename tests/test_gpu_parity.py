@@ -287,3 +287,41 @@ def test_column_split_kernel_headline_config(column_split):
     out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
     ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
     check(out, ref, cfg.dtype, "vs recurrent (all elements)")
+
+
+# ---------------------------------------------------------------- HIP graph capture
+def test_prefill_and_decode_replay_from_a_hip_graph(B):
+    """The library's launches can be captured; every replay, with eager work in between, equals eager."""
+    q, k, v, gamma = W.make_custom_forward_inputs(2, 4, 1100, 128, "bf16", 9)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    S0 = torch.empty(2, 4, 128, 128, dtype=torch.float32, device="cuda")
+    eager = B.leet_attn_forward_ex(dq, dk, dv, dg, state_out=S0, segments=3).clone()   # also sizes the workspace
+    q1, k1, v1 = (t[:, :, 0].contiguous() for t in (dq, dk, dv))
+    S_e = S0.clone()
+    o_e = B.leet_attn_decode_step(q1, k1, v1, dg, S_e).clone()
+    torch.cuda.synchronize()
+
+    out = torch.zeros_like(eager)
+    S = torch.zeros_like(S0)
+    o1 = torch.zeros_like(o_e)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.leet_attn_forward_ex(dq, dk, dv, dg, out=out, state_out=S, segments=3)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.leet_attn_forward_ex(dq, dk, dv, dg, out=out, state_out=S, segments=3)
+        B.leet_attn_decode_step(q1, k1, v1, dg, S, o1)
+    for rep in range(3):
+        out.zero_(); S.zero_(); o1.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}: prefill output differs from eager"
+        assert torch.equal(S, S_e), f"replay {rep}: state differs from eager"
+        assert torch.equal(o1, o_e), f"replay {rep}: decode output differs from eager"
+        # eager work of the program between replays
+        other = B.leet_attn_forward_ex(dq, dk, dv, dg, segments=2)   # other segment count: equal up to rounding
+        assert max_rel_err(other.cpu().numpy(), eager.cpu().numpy()) < TOL["bf16"]

@@ -26,14 +26,16 @@ namespace {
 using leet::kChunk;
 
 // Sequences are cut into segments so that about this many workgroups exist, but no
-// segment is shorter than kMinSegChunks chunks: each extra segment costs one D x D fp32
-// state written, scanned and re-read, and every segment but the last has its K and V read
-// twice.  One workgroup per compute unit of a 256-CU device measured best for both kernel
+// segment is shorter than a minimum number of chunks: each extra segment costs one D x D
+// fp32 state written, scanned and re-read, and every segment but the last has its K and V
+// read twice.  The fp32 kernel is bound by MFMA latency per chunk, not by HBM, so it takes
+// much shorter segments than the bf16 kernels.  One workgroup per compute unit of a 256-CU device measured best for both kernel
 // families (the walk is HBM-bound from there on, and fewer segments mean less pre-pass and
 // scan traffic); the column-split bf16 kernel puts D/32 workgroups on a segment.
 constexpr int kTargetWorkgroupsWide = 256;
 constexpr int kTargetWorkgroupsCoop = 256;
-constexpr int kMinSegChunks = 8;
+constexpr int kMinSegChunksBf16 = 8;
+constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 
 // Kernel choice for bf16 prefill: LEET_KERNEL_WIDE (default) or LEET_KERNEL_COLUMN_SPLIT.
@@ -56,7 +58,7 @@ bool make_plan(long BH, int N, int D, int dtype, int segments, Plan* plan) {
         want = segments;
     } else {
         want = (target + per_seg - 1) / per_seg;
-        long cap = nchunks / kMinSegChunks;
+        long cap = nchunks / (dtype == LEET_F32 ? kMinSegChunksF32 : kMinSegChunksBf16);
         if (cap < 1) cap = 1;
         if (want > cap) want = cap;
     }

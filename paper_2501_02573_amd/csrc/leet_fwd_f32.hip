@@ -1,14 +1,35 @@
-// Chunk-walk kernel for fp32 inputs (gfx950, v_mfma_f32_32x32x2_f32: true fp32 products).
+// Chunk-walk kernel for fp32 inputs (gfx950, v_mfma_f32_16x16x4_f32: true fp32 products).
 //
-// Same algorithm and work split as the bf16 kernel: one workgroup per segment of a
-// (batch, head) sequence walks 64-token chunks (Alg. 2, Appendix B.2, with the decaying
-// mask of Eq. "BCMV" and the weight split of Alg. 4); wave w owns value columns
-// [32w, 32w+32) of O and of the state S.
+// Same algorithm as the bf16 kernel: one workgroup per segment of a (batch, head) sequence
+// walks 64-token chunks (Alg. 2, Appendix B.2, with the decaying mask of Eq. "BCMV" and the
+// weight split of Alg. 4, Appendix B.3):
 //
-// The fp32 MFMA takes one contraction index per lane (lane l: row/column l%32,
-// contraction index l/32), so no operand needs a transposed copy: Q, K, V sit
-// row-major in LDS, and both the score accumulators (as P) and the state accumulators
-// (as S) feed the next MFMA straight from registers, one register per instruction.
+//     O_t     = ((Q_t K_t^T) .* D) V_t + Lam (Q_t S_t)       D[i][j] = gamma^(i-j), i >= j
+//     S_{t+1} = gamma^L S_t + (Gam K_t)^T V_t                Lam = diag(gamma^(i+1)), Gam = diag(gamma^(L-1-j))
+//
+// fp32 MFMA is 16 times slower than bf16 MFMA, so this kernel is bound by MFMA issue and
+// latency, not by HBM; the work is therefore cut finer than in the bf16 kernel: wave w owns
+// 16 value columns [16w, 16w+16) of O and of the state S (d/16 waves per workgroup), and all
+// products are 16x16x4 tiles.
+//
+// MFMA conventions (16x16x4 fp32): an A (B) operand is one float per lane: lane l holds row
+// (column) l%16 and contraction slot q = l/16; an accumulator holds, in lane l, column l%16
+// and, in register r, row 4q + r.  A contraction may assign indices to slots in any way, as
+// long as A and B agree.  Everything is computed transposed (lane = token), so that an
+// accumulator register of one product is directly an operand of the next:
+//   G1  P^T[j][i]  = sum_dk K[j][dk] Q[i][dk]        A, B: 16-byte LDS reads, 4 MFMAs each
+//       P^T       *= D^T                             per-lane weights, fixed for the kernel
+//   G3  O^T[c][i]  = sum_dk S^T[c][dk] Q^T[dk][i]    A = S accumulator registers, B = Q rows
+//       O^T       *= gamma^(i+1)                     one scalar per lane, since lane = token
+//   G2  O^T[c][i] += sum_j V^T[c][j] P^T[j][i]       A = V[j][c] for j = 16jt + 4q + r, B = P^T registers
+//   G4  S[dk][c]  += sum_j K^T[dk][j] (Gam V)[j][c]  A = K[j][dk], B = the V registers of G2 times Gam
+// The 64 x 64 score matrix has ten non-zero 16 x 16 tiles; each is computed once per workgroup
+// (tile n by wave n mod #waves), masked, and handed to the other waves through LDS in
+// operand-register order.
+//
+// A ragged last chunk (L < 64) is right-aligned in the tile: rows 64-L.. hold the tokens,
+// rows above are zero, so the intra-chunk weights (functions of i-j and of 63-j) stay valid;
+// only Lam and gamma^L depend on L.
 #include "leet_common.hpp"
 
 namespace leet {
@@ -19,20 +40,29 @@ struct F32Smem {
     float q[kChunk * RS];
     float k[kChunk * RS];
     float v[kChunk * RS];
-    float pw[kChunk + 4];
+    f32x4 pfrag[10][64];              // masked P^T tiles: [tile][lane], registers 0..3
+    float pw[kChunk + 4];             // gamma^n, n = 0..64
 };
 
+// The ten score tiles (it >= jt) in production order.
+__device__ __forceinline__ constexpr int f32_tile_it(int n) { return n < 1 ? 0 : n < 3 ? 1 : n < 6 ? 2 : 3; }
+__device__ __forceinline__ constexpr int f32_tile_jt(int n) { return n - (f32_tile_it(n) * (f32_tile_it(n) + 1)) / 2; }
+
+// kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
 template <int D, bool kOut>
-__global__ __launch_bounds__(D * 2) void fwd_f32_kernel(FwdParams p) {
-    constexpr int NT = D * 2;
-    constexpr int DT = D / 32;
+__global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
+    constexpr int NT = D * 4;                  // threads: one wave per 16 value columns
+    constexpr int NW = D / 16;                 // waves
+    constexpr int DT = D / 16;                 // 16-row tiles of the key dimension
     constexpr int RS = F32Smem<D>::RS;
     constexpr int PR = D / 4;                  // 16-byte pieces per row
-    constexpr int NLOAD = kChunk * PR / NT;    // pieces per thread per tensor (= 8)
+    constexpr int NLOAD = kChunk * PR / NT;    // pieces per thread per tensor (= 4)
+    constexpr int ROWS_PER_PASS = NT / PR;     // rows one pass of all threads covers (= 16)
+    constexpr int NSLOT = (10 + NW - 1) / NW;  // score tiles per wave, at most
     __shared__ __attribute__((aligned(16))) F32Smem<D> sm;
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63, ln = l & 31, g = l >> 5;
+    const int w = tid >> 6, l = tid & 63, ln = l & 15, qd = l >> 4;
     const int nseg_launch = kOut ? p.nseg : p.nseg - 1;
     const int bh = blockIdx.x / nseg_launch;
     const int seg = blockIdx.x % nseg_launch;
@@ -53,8 +83,9 @@ __global__ __launch_bounds__(D * 2) void fwd_f32_kernel(FwdParams p) {
         for (int n = tid; n <= kChunk; n += NT) sm.pw[n] = (float)pow_int(gd, n);
     }
 
-    f32x16 S[DT];
-    const int c_own = 32 * w + ln;
+    // state slice: S[t][r] = S[dk = 16t + 4q + r][c = 16w + ln]
+    f32x4 S[DT];
+    const int c_own = 16 * w + ln;
     {
         const float* src = nullptr;
         if (kOut) {
@@ -64,112 +95,131 @@ __global__ __launch_bounds__(D * 2) void fwd_f32_kernel(FwdParams p) {
 #pragma unroll
         for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int dk = 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                S[t][r] = src ? src[dk * D + c_own] : 0.0f;
-            }
+            for (int r = 0; r < 4; ++r) S[t][r] = src ? src[(16 * t + 4 * qd + r) * D + c_own] : 0.0f;
     }
+
+    __syncthreads();  // table visible
+
+    // per-lane constants of the walk
+    f32x4 wgt[NSLOT];   // decay weights of the score tiles this wave produces
+    float gam[16];      // gamma^(63-j) for the keys j = 16jt + 4q + r this lane feeds to G2 and G4
+#pragma unroll
+    for (int n = 0; n < 10; ++n) {
+        if (n % NW != w) continue;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int d = 16 * (f32_tile_it(n) - f32_tile_jt(n)) + ln - (4 * qd + r);  // i - j
+            wgt[n / NW][r] = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) gam[e] = sm.pw[kChunk - 1 - (16 * (e >> 2) + 4 * qd + (e & 3))];
+
+    // staging: piece r of this thread is row ROWS_PER_PASS*r + tid/PR, floats 4(tid%PR)..+3
+    const int j0 = tid / PR, cc = tid % PR;
+    f32x4 rq[NLOAD], rk[NLOAD], rv[NLOAD];
+    auto prefetch = [&](int tok0) {
+        const int shift = max(0, tok0 + kChunk - tok_end);  // rows [0, shift) of the tile stay zero
+#pragma unroll
+        for (int r = 0; r < NLOAD; ++r) {
+            const int j = ROWS_PER_PASS * r + j0;
+            const bool ok = j >= shift;
+            const size_t off = (size_t)(tok0 - shift + j) * D + cc * 4;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            if (kOut) rq[r] = ok ? *reinterpret_cast<const f32x4*>(qb + off) : z;
+            rk[r] = ok ? *reinterpret_cast<const f32x4*>(kb + off) : z;
+            rv[r] = ok ? *reinterpret_cast<const f32x4*>(vb + off) : z;
+        }
+    };
+
+    prefetch(tok_begin);
 
     for (int t = 0; t < nchunks; ++t) {
         const int tok0 = tok_begin + t * kChunk;
         const int Lc = min(kChunk, tok_end - tok0);
+        const int shift = kChunk - Lc;
 
-        __syncthreads();  // previous chunk fully consumed (and pw written, first time round)
+        if (t > 0) __syncthreads();  // everyone is done reading the previous chunk's tiles and P fragments
 #pragma unroll
         for (int r = 0; r < NLOAD; ++r) {
-            int piece = r * NT + tid;
-            int j = piece / PR, cc = piece % PR;
-            bool ok = tok0 + j < tok_end;
-            size_t off = (size_t)(tok0 + j) * D + cc * 4;
-            f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            if (kOut) *reinterpret_cast<f32x4*>(&sm.q[j * RS + cc * 4]) = ok ? *reinterpret_cast<const f32x4*>(qb + off) : z;
-            *reinterpret_cast<f32x4*>(&sm.k[j * RS + cc * 4]) = ok ? *reinterpret_cast<const f32x4*>(kb + off) : z;
-            *reinterpret_cast<f32x4*>(&sm.v[j * RS + cc * 4]) = ok ? *reinterpret_cast<const f32x4*>(vb + off) : z;
+            const int j = ROWS_PER_PASS * r + j0;
+            if (kOut) *reinterpret_cast<f32x4*>(&sm.q[j * RS + cc * 4]) = rq[r];
+            *reinterpret_cast<f32x4*>(&sm.k[j * RS + cc * 4]) = rk[r];
+            *reinterpret_cast<f32x4*>(&sm.v[j * RS + cc * 4]) = rv[r];
         }
         __syncthreads();
+        if (t + 1 < nchunks) prefetch(tok0 + kChunk);  // in flight during the MFMA work below
 
+        f32x4 o[4];
         if (kOut) {
-            f32x16 o[2];
+            // G1 + mask for the score tiles this wave produces
 #pragma unroll
-            for (int it = 0; it < 2; ++it)
+            for (int n = 0; n < 10; ++n) {
+                if (n % NW != w) continue;
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                const float* krow = &sm.k[(16 * f32_tile_jt(n) + ln) * RS + 4 * qd];
+                const float* qrow = &sm.q[(16 * f32_tile_it(n) + ln) * RS + 4 * qd];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[it][r] = 0.0f;
-
-            // ---- inter-chunk term O = Q_t S_t (register r of S[dt] is contraction step r), rows * gamma^(i+1)
+                for (int s = 0; s < D / 16; ++s) {
+                    const f32x4 a = *reinterpret_cast<const f32x4*>(krow + 16 * s);
+                    const f32x4 b = *reinterpret_cast<const f32x4*>(qrow + 16 * s);
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-#pragma unroll
-                    for (int it = 0; it < 2; ++it) {
-                        f32x4 a = *reinterpret_cast<const f32x4*>(&sm.q[(32 * it + ln) * RS + 32 * dt + 8 * rq + 4 * g]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            o[it] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], S[dt][4 * rq + e], o[it], 0, 0, 0);
-                    }
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int i = 32 * it + 8 * (r >> 2) + 4 * g + (r & 3);
-                    o[it][r] *= sm.pw[i + 1];
+                    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e], b[e], acc, 0, 0, 0);
                 }
+                sm.pfrag[n][l] = acc * wgt[n / NW];
+            }
 
-            // ---- intra-chunk term: P^T = K Q^T, decay mask, O += P V
+            // G3: O^T = S^T Q^T, rows of O scaled by gamma^(i+1)
 #pragma unroll
-            for (int it = 0; it < 2; ++it)
+            for (int it = 0; it < 4; ++it) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                const float* qrow = &sm.q[(16 * it + ln) * RS + 4 * qd];
 #pragma unroll
-                for (int jt = 0; jt <= it; ++jt) {
-                    f32x16 acc;
+                for (int dt = 0; dt < DT; ++dt) {
+                    const f32x4 b = *reinterpret_cast<const f32x4*>(qrow + 16 * dt);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-                    for (int u = 0; u < D / 8; ++u) {
-                        f32x4 a = *reinterpret_cast<const f32x4*>(&sm.k[(32 * jt + ln) * RS + 8 * u + 4 * g]);
-                        f32x4 b = *reinterpret_cast<const f32x4*>(&sm.q[(32 * it + ln) * RS + 8 * u + 4 * g]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        int n = 32 * (it - jt) + ln - (8 * (r >> 2) + 4 * g + (r & 3));  // i - j
-                        float wgt = sm.pw[max(n, 0)];
-                        acc[r] = (n >= 0) ? acc[r] * wgt : 0.0f;
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        int j = 32 * jt + 8 * (r >> 2) + 4 * g + (r & 3);
-                        o[it] = __builtin_amdgcn_mfma_f32_32x32x2f32(acc[r], sm.v[j * RS + c_own], o[it], 0, 0, 0);
-                    }
+                    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(S[dt][e], b[e], acc, 0, 0, 0);
                 }
-
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int i = 32 * it + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (i < Lc) ob[(size_t)(tok0 + i) * D + c_own] = o[it][r];
-                }
+                o[it] = acc * sm.pw[max(16 * it + ln + 1 - shift, 0)];
+            }
         }
 
-        // ---- state update: S = gamma^L S + (Gam K)^T V ; contraction step u covers tokens 2u, 2u+1
+        // V registers: va[4jt + r] = V[j = 16jt + 4q + r][c_own]
+        float va[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) va[e] = sm.v[(16 * (e >> 2) + 4 * qd + (e & 3)) * RS + c_own];
+
+        if (kOut) {
+            __syncthreads();  // P fragments visible
+            // G2: O^T += V^T P^T over the tiles (jt <= it)
+#pragma unroll
+            for (int n = 0; n < 10; ++n) {
+                const f32x4 pt = sm.pfrag[n][l];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    o[f32_tile_it(n)] = __builtin_amdgcn_mfma_f32_16x16x4f32(va[4 * f32_tile_jt(n) + r], pt[r],
+                                                                            o[f32_tile_it(n)], 0, 0, 0);
+            }
+            // store O^T: lane = token 16it + ln, registers = columns 16w + 4q + (0..3)
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int i = 16 * it + ln;
+                if (i >= shift) *reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 16 * w + 4 * qd) = o[it];
+            }
+        }
+
+        // G4: S = gamma^L S + K^T (Gam V); contraction slot q of step (jt, r) is key 16jt + 4q + r
         {
             const float gl = sm.pw[Lc];
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt) S[dt] *= gl;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) S[dt][r] *= gl;
-#pragma unroll 8
-            for (int u = 0; u < kChunk / 2; ++u) {
-                const int j = 2 * u + g;
-                const float sc = sm.pw[max(Lc - 1 - j, 0)];
-                const float b = sm.v[j * RS + c_own];
+            for (int e = 0; e < 16; ++e) {
+                const float b = va[e] * gam[e];
+                const float* krow = &sm.k[(16 * (e >> 2) + 4 * qd + (e & 3)) * RS + ln];
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    float a = sm.k[j * RS + 32 * dt + ln] * sc;
-                    S[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, S[dt], 0, 0, 0);
-                }
+                for (int dt = 0; dt < DT; ++dt)
+                    S[dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(krow[16 * dt], b, S[dt], 0, 0, 0);
             }
         }
     }
@@ -184,23 +234,20 @@ __global__ __launch_bounds__(D * 2) void fwd_f32_kernel(FwdParams p) {
 #pragma unroll
         for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int dk = 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
-                dst[dk * D + c_own] = S[t][r];
-            }
+            for (int r = 0; r < 4; ++r) dst[(16 * t + 4 * qd + r) * D + c_own] = S[t][r];
     }
 }
 
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream) {
     if (p.nseg <= 1) return hipSuccess;
-    if (D == 64) hipLaunchKernelGGL((fwd_f32_kernel<64, false>), dim3(BH * (p.nseg - 1)), dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((fwd_f32_kernel<128, false>), dim3(BH * (p.nseg - 1)), dim3(256), 0, stream, p);
+    if (D == 64) hipLaunchKernelGGL((fwd_f32_kernel<64, false>), dim3(BH * (p.nseg - 1)), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((fwd_f32_kernel<128, false>), dim3(BH * (p.nseg - 1)), dim3(512), 0, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream) {
-    if (D == 64) hipLaunchKernelGGL((fwd_f32_kernel<64, true>), dim3(BH * p.nseg), dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((fwd_f32_kernel<128, true>), dim3(BH * p.nseg), dim3(256), 0, stream, p);
+    if (D == 64) hipLaunchKernelGGL((fwd_f32_kernel<64, true>), dim3(BH * p.nseg), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((fwd_f32_kernel<128, true>), dim3(BH * p.nseg), dim3(512), 0, stream, p);
     return hipGetLastError();
 }
 

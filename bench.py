@@ -14,6 +14,9 @@ once into a HIP graph and replayed (reported for comparison, it measured no fast
 ``roofline`` is for the dominant kernel (the chunk walk), whose per-launch duration is measured
 with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle (recurrent form)
 timed on this host's cores on the same workload.
+
+Defaults: 100 warm-up steps and 500 timed steps (about 60 ms of GPU work for the headline leg).
+Much shorter runs end before the device clocks have settled and read about 10 % slower.
 """
 from __future__ import annotations
 
@@ -34,8 +37,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
     ap.add_argument("--no-graph", action="store_true", help="time plain calls only (no HIP graph replay)")

@@ -42,14 +42,26 @@ extern "C" {
 #endif
 
 typedef enum {
-    LEET_F32 = 0, /* q, k, v are IEEE binary32; products on fp32 MFMA            */
-    LEET_BF16 = 1 /* q, k, v are bfloat16; products on bf16 MFMA, fp32 accumulate */
+    LEET_F32 = 0,  /* q, k, v are IEEE binary32; products on fp32 MFMA              */
+    LEET_BF16 = 1, /* q, k, v are bfloat16; products on bf16 MFMA, fp32 accumulate  */
+    LEET_F16 = 2   /* q, k, v are IEEE binary16; products on fp16 MFMA, fp32 accumulate
+                      (accepted by the _v2 entry points only)                      */
 } leet_dtype;
+
+/*
+ * Which mask M the operator uses (Section 2.2: the decaying mask of Eq. "BCMV", or the 0/1
+ * causal mask of plain causal linear attention, which is the same operator with gamma = 1).
+ */
+typedef enum {
+    LEET_MASK_DECAY = 0, /* M[i][j] = gamma_h^(i-j), i >= j; `gamma` is read                  */
+    LEET_MASK_CAUSAL = 1 /* M[i][j] = 1, i >= j; `gamma` is ignored and may be NULL; kernels
+                            specialised to skip every decay multiplication                 */
+} leet_mask;
 
 typedef enum {
     LEET_OK = 0,
     LEET_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, misaligned pointer, workspace too small */
-    LEET_ERR_UNSUPPORTED = 2, /* d not in {64, 128}, unknown dtype, no gfx950 device */
+    LEET_ERR_UNSUPPORTED = 2, /* d not in {64, 128}, unknown dtype or dtype combination, no gfx950 device */
     LEET_ERR_LAUNCH = 3,      /* the HIP runtime refused a launch or an allocation */
     LEET_ERR_TOO_LARGE = 4    /* sizes overflow the library's index range */
 } leet_status;
@@ -104,6 +116,27 @@ int leet_attn_forward_ex(const void *q, const void *k, const void *v, const floa
                          const float *state_in, float *state_out,
                          void *workspace, size_t workspace_bytes, int segments,
                          int B, int H, int N, int d, int dtype, void *stream);
+
+/*
+ * Chunked prefill with every option: as leet_attn_forward_ex, and additionally
+ *   in_dtype   LEET_F32, LEET_BF16 or LEET_F16 (the paper's methods take fp16 and fp32 inputs,
+ *              Section 4; bf16 is this library's headline type)
+ *   out_dtype  LEET_F32, or, for 16-bit inputs, the input type: `out` is then [B][H][N][d] of
+ *              that type, rounded to nearest even from the fp32 accumulators (halves the
+ *              output traffic of an HBM-bound kernel)
+ *   mask       a leet_mask
+ * Any other combination returns LEET_ERR_UNSUPPORTED.  States stay fp32.  The column-split
+ * kernel (leet_attn_set_bf16_kernel) is used only for bf16 in, fp32 out, decaying mask.
+ */
+int leet_attn_forward_v2(const void *q, const void *k, const void *v, const float *gamma, void *out,
+                         const float *state_in, float *state_out,
+                         void *workspace, size_t workspace_bytes, int segments,
+                         int B, int H, int N, int d, int in_dtype, int out_dtype, int mask, void *stream);
+
+/* As leet_attn_decode_step_ex, with `dtype` also LEET_F16 and with a leet_mask. */
+int leet_attn_decode_step_v2(const void *q, const void *k, const void *v, const float *gamma,
+                             float *state_inout, float *out, int B, int H, int d, int dtype, int mask,
+                             void *stream);
 
 /*
  * Measurement aid: computes what leet_attn_forward_ex computes, with HIP events recorded on

@@ -17,7 +17,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libleet_attn.so")
 
-LEET_F32, LEET_BF16 = 0, 1
+LEET_F32, LEET_BF16, LEET_F16 = 0, 1, 2
+LEET_MASK_DECAY, LEET_MASK_CAUSAL = 0, 1
 LEET_OK, LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED, LEET_ERR_LAUNCH, LEET_ERR_TOO_LARGE = 0, 1, 2, 3, 4
 
 EXPORTED_SYMBOLS = (
@@ -25,6 +26,8 @@ EXPORTED_SYMBOLS = (
     "leet_attn_decode_step",
     "leet_attn_decode_step_ex",
     "leet_attn_forward_ex",
+    "leet_attn_forward_v2",
+    "leet_attn_decode_step_v2",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
@@ -53,6 +56,10 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_forward.restype = i
     lib.leet_attn_forward_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp]
     lib.leet_attn_forward_ex.restype = i
+    lib.leet_attn_forward_v2.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_v2.restype = i
+    lib.leet_attn_decode_step_v2.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+    lib.leet_attn_decode_step_v2.restype = i
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
@@ -93,7 +100,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return LEET_F32
     if t.dtype == torch.bfloat16:
         return LEET_BF16
-    raise TypeError(f"unsupported dtype {t.dtype}: q, k, v must be float32 or bfloat16")
+    if t.dtype == torch.float16:
+        return LEET_F16
+    raise TypeError(f"unsupported dtype {t.dtype}: q, k, v must be float32, bfloat16 or float16")
 
 
 def _check_dev(*tensors: Optional[torch.Tensor]) -> torch.device:
@@ -143,15 +152,15 @@ def release_workspace() -> None:
         raise LeetAttnError(st, "leet_attn_release_workspace")
 
 
-def _check_forward(q, k, v, gamma, out):
+def _check_forward(q, k, v, gamma, out, any_out_dtype: bool = False):
     if q.dim() != 4 or q.shape != k.shape or q.shape != v.shape:
         raise ValueError("q, k, v must share one [B, H, N, d] shape")
     if k.dtype != q.dtype or v.dtype != q.dtype:
         raise TypeError("q, k, v must share one dtype")
     B, H, N, d = q.shape
-    if gamma.dtype != torch.float32 or gamma.numel() != H:
+    if gamma is not None and (gamma.dtype != torch.float32 or gamma.numel() != H):
         raise ValueError("gamma must be float32 with one value per head")
-    if out.dtype != torch.float32 or out.shape != q.shape:
+    if out.shape != q.shape or (out.dtype != torch.float32 and not any_out_dtype):
         raise ValueError("out must be float32 [B, H, N, d]")
     return B, H, N, d
 
@@ -197,6 +206,39 @@ def leet_attn_forward_ex(q, k, v, gamma, out: Optional[torch.Tensor] = None,
     return out
 
 
+def leet_attn_forward_v2(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                         state_in: Optional[torch.Tensor] = None,
+                         state_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, segments: int = 0,
+                         out_dtype: Optional[torch.dtype] = None,
+                         mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """Chunked prefill with every option: fp16 inputs, output in the input type, 0/1 causal mask.
+
+    ``out_dtype`` (used when ``out`` is None) defaults to float32; ``gamma`` may be None with
+    ``mask=LEET_MASK_CAUSAL``.  Unsupported combinations are reported by the library.
+    """
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype or torch.float32, device=q.device)
+    B, H, N, d = _check_forward(q, k, v, gamma, out, any_out_dtype=True)
+    for name, s in (("state_in", state_in), ("state_out", state_out)):
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != (B, H, d, d)):
+            raise ValueError(f"{name} must be float32 [B, H, d, d]")
+    ws_bytes = 0
+    if workspace is not None:
+        if workspace.dtype != torch.uint8:
+            raise TypeError("workspace must be a uint8 tensor")
+        ws_bytes = workspace.numel()
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out, workspace)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_v2(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                      _ptr(state_out), _ptr(workspace), ws_bytes, int(segments),
+                                      B, H, N, d, _dtype_code(q), _dtype_code(out), int(mask),
+                                      ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_v2")
+    return out
+
+
 def leet_attn_forward_profile(q, k, v, gamma, out: Optional[torch.Tensor] = None, segments: int = 0):
     """One prefill with per-kernel HIP-event timing; returns (out, [pre-pass ms, scan ms, walk ms])."""
     if out is None:
@@ -231,7 +273,7 @@ def _check_decode(q, k, v, gamma, state, out):
     if k.dtype != q.dtype or v.dtype != q.dtype:
         raise TypeError("q, k, v must share one dtype")
     B, H, d = q.shape
-    if gamma.dtype != torch.float32 or gamma.numel() != H:
+    if gamma is not None and (gamma.dtype != torch.float32 or gamma.numel() != H):
         raise ValueError("gamma must be float32 with one value per head")
     if state.dtype != torch.float32 or tuple(state.shape) != (B, H, d, d):
         raise ValueError("state must be float32 [B, H, d, d]")
@@ -267,4 +309,19 @@ def leet_attn_decode_step_ex(q, k, v, gamma, state, out: Optional[torch.Tensor] 
                                           B, H, d, _dtype_code(q), ctypes.c_void_p(_stream_ptr(dev)))
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_decode_step_ex")
+    return out
+
+
+def leet_attn_decode_step_v2(q, k, v, gamma: Optional[torch.Tensor], state, out: Optional[torch.Tensor] = None,
+                             mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """One decode step with float32, bfloat16 or float16 q, k, v and either mask."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, d = _check_decode(q, k, v, gamma, state, out)
+    dev = _check_dev(q, k, v, gamma, state, out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_decode_step_v2(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                          B, H, d, _dtype_code(q), int(mask), ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_decode_step_v2")
     return out

@@ -9,8 +9,8 @@
 #include "leet_common.hpp"
 
 namespace leet {
-hipError_t launch_fwd_bf16_states(const FwdParams& p, int BH, int D, hipStream_t stream);
-hipError_t launch_fwd_bf16_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream);
+hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_bf16_coop_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
@@ -18,7 +18,7 @@ hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t st
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
                            int nseg, int seg_tokens, int D, hipStream_t stream);
 hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
-                         float* out, int BH, int H, int D, bool bf16, hipStream_t stream);
+                         float* out, int BH, int H, int D, int elem, hipStream_t stream);
 }  // namespace leet
 
 namespace {
@@ -46,11 +46,14 @@ struct Plan {
     int nseg;
     int seg_chunks;
     size_t ws_bytes;
+    bool coop;  // the column-split kernel runs this call
 };
 
-bool make_plan(long BH, int N, int D, int dtype, int segments, Plan* plan) {
+// plain = fp32 output and decaying mask, the only form the column-split kernel implements
+bool make_plan(long BH, int N, int D, int dtype, bool plain, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
-    const bool coop = dtype == LEET_BF16 && use_coop_kernel();
+    const bool coop = dtype == LEET_BF16 && plain && use_coop_kernel();
+    plan->coop = coop;
     const long per_seg = coop ? BH * (D / 32) : BH;   // workgroups one segment of every sequence gives
     const long target = coop ? kTargetWorkgroupsCoop : kTargetWorkgroupsWide;
     long want;
@@ -76,7 +79,7 @@ bool make_plan(long BH, int N, int D, int dtype, int segments, Plan* plan) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool shape_ok(int d, int dtype, int* status) {
-    if (dtype != LEET_F32 && dtype != LEET_BF16) { *status = LEET_ERR_UNSUPPORTED; return false; }
+    if (dtype != LEET_F32 && dtype != LEET_BF16 && dtype != LEET_F16) { *status = LEET_ERR_UNSUPPORTED; return false; }
     if (d != 64 && d != 128) { *status = LEET_ERR_UNSUPPORTED; return false; }
     return true;
 }
@@ -119,13 +122,19 @@ int own_workspace(int dev, size_t bytes, void** out) {
     return LEET_OK;
 }
 
-int forward_impl(const void* q, const void* k, const void* v, const float* gamma, float* out,
+int forward_impl(const void* q, const void* k, const void* v, const float* gamma, void* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
-                 int segments, int B, int H, int N, int d, int dtype, void* stream, float* kernel_ms) {
-    if (!q || !k || !v || !gamma || !out) return LEET_ERR_INVALID_ARG;
+                 int segments, int B, int H, int N, int d, int dtype, int out_dtype, int mask, void* stream,
+                 float* kernel_ms) {
+    if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
+    const bool no_decay = mask == LEET_MASK_CAUSAL;
+    if (!q || !k || !v || !out || (!gamma && !no_decay)) return LEET_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
     if (!shape_ok(d, dtype, &status)) return status;
+    // the output is fp32, or, for 16-bit inputs, the input type
+    if (out_dtype != LEET_F32 && (out_dtype != dtype || dtype == LEET_F32)) return LEET_ERR_UNSUPPORTED;
+    if (no_decay) gamma = nullptr;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
         !aligned16(state_out) || (reinterpret_cast<uintptr_t>(gamma) & 3u))
         return LEET_ERR_INVALID_ARG;
@@ -134,7 +143,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dtype, out_dtype == LEET_F32 && !no_decay, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -155,13 +164,16 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     p.state_in = state_in; p.state_out = state_out;
     p.seg_state = static_cast<float*>(ws);
     p.H = H; p.N = N; p.nseg = plan.nseg; p.seg_chunks = plan.seg_chunks;
+    p.no_decay = no_decay ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool bf16 = dtype == LEET_BF16;
+    const bool in16 = dtype != LEET_F32;
+    const bool f16 = dtype == LEET_F16;
+    const bool out16 = out_dtype != LEET_F32;
 
-    const bool coop = bf16 && use_coop_kernel();
+    const bool coop = plan.coop;
     auto launch_states = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
-               : bf16 ? leet::launch_fwd_bf16_states(p, (int)BH, d, s)
+               : in16 ? leet::launch_fwd_16bit_states(p, (int)BH, d, f16, s)
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
     auto launch_scan = [&]() {
@@ -169,7 +181,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     };
     auto launch_walk = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
-               : bf16 ? leet::launch_fwd_bf16_walk(p, (int)BH, d, s)
+               : in16 ? leet::launch_fwd_16bit_walk(p, (int)BH, d, f16, out16, s)
                       : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
     };
 
@@ -220,14 +232,25 @@ extern "C" {
 
 int leet_attn_forward(const void* q, const void* k, const void* v, const float* gamma, float* out,
                       int B, int H, int N, int d, int dtype, void* stream) {
-    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, stream, nullptr);
+    if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;  // fp16 inputs go through leet_attn_forward_v2
+    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, LEET_F32,
+                        LEET_MASK_DECAY, stream, nullptr);
 }
 
 int leet_attn_forward_ex(const void* q, const void* k, const void* v, const float* gamma, float* out,
                          const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
                          int segments, int B, int H, int N, int d, int dtype, void* stream) {
+    if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, dtype, stream, nullptr);
+                        B, H, N, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, nullptr);
+}
+
+int leet_attn_forward_v2(const void* q, const void* k, const void* v, const float* gamma, void* out,
+                         const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                         int segments, int B, int H, int N, int d, int in_dtype, int out_dtype, int mask,
+                         void* stream) {
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
+                        B, H, N, d, in_dtype, out_dtype, mask, stream, nullptr);
 }
 
 int leet_attn_forward_profile(const void* q, const void* k, const void* v, const float* gamma, float* out,
@@ -235,21 +258,25 @@ int leet_attn_forward_profile(const void* q, const void* k, const void* v, const
                               int segments, int B, int H, int N, int d, int dtype, void* stream,
                               float* kernel_ms) {
     if (!kernel_ms) return LEET_ERR_INVALID_ARG;
+    if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, dtype, stream, kernel_ms);
+                        B, H, N, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, kernel_ms);
 }
 
 size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(d, dtype, &status)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, dtype, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, d, dtype, true, segments, &plan)) return 0;
     return plan.ws_bytes;
 }
 
-int leet_attn_decode_step_ex(const void* q, const void* k, const void* v, const float* gamma,
-                             float* state_inout, float* out, int B, int H, int d, int dtype, void* stream) {
-    if (!q || !k || !v || !gamma || !state_inout || !out) return LEET_ERR_INVALID_ARG;
+int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dtype, int mask,
+                             void* stream) {
+    if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
+    if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
+    if (!q || !k || !v || (!gamma && mask == LEET_MASK_DECAY) || !state_inout || !out) return LEET_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || d <= 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
     if (!shape_ok(d, dtype, &status)) return status;
@@ -262,9 +289,15 @@ int leet_attn_decode_step_ex(const void* q, const void* k, const void* v, const 
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
-    hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, dtype == LEET_BF16,
+    const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
+    hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, elem,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
+int leet_attn_decode_step_ex(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dtype, void* stream) {
+    return leet_attn_decode_step_v2(q, k, v, gamma, state_inout, out, B, H, d, dtype, LEET_MASK_DECAY, stream);
 }
 
 int leet_attn_decode_step(const void* q, const void* k, const void* v, const float* gamma,
@@ -288,7 +321,7 @@ const char* leet_attn_strerror(int status) {
     switch (status) {
         case LEET_OK: return "ok";
         case LEET_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive size, misaligned pointer or workspace too small)";
-        case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128, dtype f32 or bf16, device gfx950)";
+        case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128; dtype f32, bf16 or f16; output fp32 or the 16-bit input type; device gfx950)";
         case LEET_ERR_LAUNCH: return "HIP runtime error (launch or allocation failed)";
         case LEET_ERR_TOO_LARGE: return "sizes exceed the library's index range";
         default: return "unknown status";
@@ -303,6 +336,6 @@ int leet_attn_set_bf16_kernel(int which) {
 
 int leet_attn_get_bf16_kernel(void) { return g_bf16_kernel.load(std::memory_order_relaxed); }
 
-const char* leet_attn_version(void) { return "0.2.0"; }
+const char* leet_attn_version(void) { return "0.3.0"; }
 
 }  // extern "C"

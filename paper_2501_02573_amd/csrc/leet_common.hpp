@@ -12,6 +12,9 @@ constexpr int kChunk = 64;  // tokens per chunk (the block size B_c of Alg. 2; B
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -21,8 +24,8 @@ struct FwdParams {
     const void* q;          // [BH][N][D]
     const void* k;
     const void* v;
-    const float* gamma;     // [H]
-    float* out;             // [BH][N][D]
+    const float* gamma;     // [H]; not read when no_decay
+    void* out;              // [BH][N][D], fp32 or the 16-bit input type
     const float* state_in;  // [BH][D][D] or null: state before token 0
     float* state_out;       // [BH][D][D] or null: state after token N-1
     float* seg_state;       // [BH][nseg-1][D][D]: slot s-1 holds the state entering segment s
@@ -30,6 +33,7 @@ struct FwdParams {
     int N;
     int nseg;        // segments per sequence
     int seg_chunks;  // chunks per segment (all but the last segment)
+    int no_decay;    // non-zero: 0/1 causal mask, i.e. gamma = 1 for every head
 };
 
 // gamma^n for integer n >= 0 in fp64 by binary exponentiation; 0^0 = 1.
@@ -43,19 +47,34 @@ __device__ __forceinline__ double pow_int(double g, int n) {
     return r;
 }
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
-    return __uint_as_float(bits16 << 16);
-}
+// The two 16-bit input types of the MFMA kernels.  Operands travel as raw 128-bit
+// registers (eight elements); only the conversions and the MFMA opcode differ.
+struct ElemBf16 {
+    static __device__ __forceinline__ float lo(uint32_t word) { return __uint_as_float(word << 16); }
+    static __device__ __forceinline__ float hi(uint32_t word) { return __uint_as_float(word & 0xffff0000u); }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+        bf16x2 r = {(__bf16)a, (__bf16)b};
+        return __builtin_bit_cast(uint32_t, r);
+    }
+    static __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
 
-// Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
-    uint32_t u = __float_as_uint(x);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
-}
+struct ElemF16 {
+    static __device__ __forceinline__ float lo(uint32_t word) {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(word & 0xffffu));
+    }
+    static __device__ __forceinline__ float hi(uint32_t word) {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(word >> 16));
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+        f16x2 r = {(_Float16)a, (_Float16)b};
+        return __builtin_bit_cast(uint32_t, r);
+    }
+    static __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
 
 }  // namespace leet

@@ -1,4 +1,7 @@
-// Chunk-walk kernel for bf16 inputs (gfx950, v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+// Chunk-walk kernel for 16-bit inputs, bf16 or fp16 (gfx950, v_mfma_f32_32x32x16_{bf16,f16},
+// fp32 accumulate), with fp32 output or output in the input type, and with the decaying mask
+// or, as a compile-time special case that drops all decay arithmetic, the 0/1 causal mask
+// (gamma = 1, the plain causal linear attention of Section 2.2).
 //
 // One workgroup walks the 64-token chunks of one segment of one (batch, head)
 // sequence in order (the loop of Alg. 2, Appendix B.2), carrying the d x d state S
@@ -11,7 +14,7 @@
 // Work split: wave w owns value columns [32w, 32w+32): it keeps S[:, cols] (D x 32
 // fp32) in accumulators for the whole walk and computes O_t[:, cols].  The 64 x 64
 // score matrix has three non-zero 32 x 32 tiles; each is computed once per workgroup
-// (tile n by wave n mod #waves), masked, packed to bf16 and handed to the other waves
+// (tile n by wave n mod #waves), masked, packed to 16 bits and handed to the other waves
 // through a small LDS buffer laid out in operand-register order.
 //
 // MFMA conventions (32x32x16): an A (B) operand register set holds, in lane l, row
@@ -22,7 +25,7 @@
 // Data flow per chunk; Q, K, V sit row-major in LDS and are never transposed in memory:
 //   G1  P^T[j][i]  = sum_dk K[j][dk] Q[i][dk]        A = K rows, B = Q rows (16-byte LDS reads)
 //       P^T       *= D^T                             per-lane weights, fixed for the kernel
-//   G3  O^T[c][i]  = sum_dk S^T[c][dk] Q^T[dk][i]    A = S accumulators (packed to bf16), B = Q rows
+//   G3  O^T[c][i]  = sum_dk S^T[c][dk] Q^T[dk][i]    A = S accumulators (packed to 16 bits), B = Q rows
 //       O^T       *= gamma^(i+1)                     one scalar per lane, since lane = token
 //   G2  O^T[c][i] += sum_j V^T[c][j] P^T[j][i]       A = V through transposing LDS reads
 //                                                    (ds_read_b64_tr_b16), B = packed P^T
@@ -57,9 +60,7 @@ struct Bf16Smem {
     float gw[kChunk];                   // gamma^(63-j)
 };
 
-__device__ __forceinline__ bf16x8 frag16(const uint16_t* p) {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p));
-}
+__device__ __forceinline__ u32x4 frag16(const uint16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
 
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element i%4 of
 // the 8-byte rows addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4 of the group.
@@ -69,29 +70,29 @@ __device__ __forceinline__ u32x2 lds_tr(const uint16_t* p) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-__device__ __forceinline__ bf16x8 join(u32x2 a, u32x2 b) {
+__device__ __forceinline__ u32x4 join(u32x2 a, u32x2 b) {
     u32x4 r = {a.x, a.y, b.x, b.y};
-    return __builtin_bit_cast(bf16x8, r);
-}
-
-// registers 8h .. 8h+7 of an accumulator tile -> bf16 operand
-__device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int h) {
-    bf16x8 r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (__bf16)acc[8 * h + e];
     return r;
 }
 
-// eight bf16 values times eight fp32 weights -> bf16
-__device__ __forceinline__ bf16x8 scale8(bf16x8 x, f32x4 w0, f32x4 w1) {
-    u32x4 u = __builtin_bit_cast(u32x4, x);
-    bf16x8 r;
+// registers 8h .. 8h+7 of an accumulator tile -> 16-bit operand
+template <typename E>
+__device__ __forceinline__ u32x4 pack_half(const f32x16& acc, int h) {
+    u32x4 r;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        uint32_t word = u[e >> 1];
-        float f = (e & 1) ? __uint_as_float(word & 0xffff0000u) : __uint_as_float(word << 16);
-        float wgt = (e < 4) ? w0[e & 3] : w1[e & 3];
-        r[e] = (__bf16)(f * wgt);
+    for (int e = 0; e < 4; ++e) r[e] = E::pack2(acc[8 * h + 2 * e], acc[8 * h + 2 * e + 1]);
+    return r;
+}
+
+// eight 16-bit values times eight fp32 weights -> 16-bit
+template <typename E>
+__device__ __forceinline__ u32x4 scale8(u32x4 x, f32x4 w0, f32x4 w1) {
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float wl = (e < 2) ? w0[2 * e] : w1[2 * e - 4];
+        const float wh = (e < 2) ? w0[2 * e + 1] : w1[2 * e - 3];
+        r[e] = E::pack2(E::lo(x[e]) * wl, E::hi(x[e]) * wh);
     }
     return r;
 }
@@ -102,8 +103,10 @@ __device__ __forceinline__ constexpr int tile_it(int n) { return n == 0 ? 0 : 1;
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment
 // pre-pass: the end state of a segment started from zero).
-template <int D, bool kOut>
-__global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
+// E: input element type.  kOut16: O is stored in the input type instead of fp32.
+// kDecay = false: every gamma is 1, so the tables, Lam, Gam and gamma^L all drop out.
+template <int D, bool kOut, typename E, bool kOut16, bool kDecay>
+__global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
     constexpr int NT = D * 2;    // threads: one wave per 32 value columns
     constexpr int NW = D / 32;   // waves
     constexpr int DT = D / 32;   // 32-row tiles of the key dimension
@@ -126,10 +129,11 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
     const uint16_t* qb = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
     const uint16_t* kb = reinterpret_cast<const uint16_t*>(p.k) + seq_off;
     const uint16_t* vb = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
-    float* ob = p.out + seq_off;
+    float* ob = static_cast<float*>(p.out) + seq_off;            // kOut16 = false
+    uint16_t* ob16 = static_cast<uint16_t*>(p.out) + seq_off;    // kOut16 = true
 
     // decay tables, fp64 -> fp32 once per workgroup
-    {
+    if (kDecay) {
         const double gd = (double)p.gamma[h];
         for (int n = tid; n <= kChunk; n += NT) {
             float x = (float)pow_int(gd, n);
@@ -184,8 +188,8 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int n = ln - (8 * (r >> 2) + 4 * g + (r & 3));
-            float diag = (n >= 0) ? sm.pw[max(n, 0)] : 0.0f;
-            float below = sm.pw[32 + n];
+            float diag = (n >= 0) ? (kDecay ? sm.pw[max(n, 0)] : 1.0f) : 0.0f;
+            float below = kDecay ? sm.pw[32 + n] : 1.0f;
             if (kBothSets) {
                 wgt[0][r] = diag;
                 wgt[kBothSets ? 1 : 0][r] = below;
@@ -193,8 +197,8 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
                 wgt[0][r] = (w == 2) ? below : diag;
             }
         }
-        lam_full[0] = sm.pw[ln + 1];
-        lam_full[1] = sm.pw[32 + ln + 1];
+        lam_full[0] = kDecay ? sm.pw[ln + 1] : 1.0f;
+        lam_full[1] = kDecay ? sm.pw[32 + ln + 1] : 1.0f;
     }
 
     u32x4 rq[4], rk[4], rv[4];
@@ -243,19 +247,20 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
                 for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
                 for (int s = 0; s < D / 16; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag16(k_row + 32 * tile_jt(n) * RSK + 16 * s),
-                                                                 frag16(q_row + 32 * tile_it(n) * RSQ + 16 * s),
-                                                                 acc, 0, 0, 0);
-                const f32x16& wt = wgt[(kBothSets && n == 2) ? 1 : 0];
+                    acc = E::mfma32(frag16(k_row + 32 * tile_jt(n) * RSK + 16 * s),
+                                    frag16(q_row + 32 * tile_it(n) * RSQ + 16 * s), acc);
+                if (kDecay || n != 2) {  // without decay the tile below the diagonal needs no weights
+                    const f32x16& wt = wgt[(kBothSets && n == 2) ? 1 : 0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] *= wt[r];
-                sm.pfrag[n][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
-                sm.pfrag[n][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
+                    for (int r = 0; r < 16; ++r) acc[r] *= wt[r];
+                }
+                sm.pfrag[n][0][l] = pack_half<E>(acc, 0);
+                sm.pfrag[n][1][l] = pack_half<E>(acc, 1);
             }
 
             // G3: O^T = S^T Q^T, rows of O scaled by gamma^(i+1)
             float lam[2] = {lam_full[0], lam_full[1]};
-            if (shift) {
+            if (kDecay && shift) {
                 lam[0] = sm.pw[max(ln + 1 - shift, 0)];
                 lam[1] = sm.pw[max(32 + ln + 1 - shift, 0)];
             }
@@ -265,20 +270,20 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
                 for (int r = 0; r < 16; ++r) o[it][r] = 0.0f;
 #pragma unroll
             for (int s = 0; s < D / 16; ++s) {
-                const bf16x8 sa = pack_half(S[s >> 1], s & 1);
+                const u32x4 sa = pack_half<E>(S[s >> 1], s & 1);
+#pragma unroll
+                for (int it = 0; it < 2; ++it) o[it] = E::mfma32(sa, frag16(q_row + 32 * it * RSQ + 16 * s), o[it]);
+            }
+            if (kDecay) {
 #pragma unroll
                 for (int it = 0; it < 2; ++it)
-                    o[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa, frag16(q_row + 32 * it * RSQ + 16 * s), o[it],
-                                                                   0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[it][r] *= lam[it];
             }
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[it][r] *= lam[it];
         }
 
         // V fragments: vf[f], f = 2*jt + hh, holds keys 16f + {4g..4g+3, 8+4g..8+4g+3} of column c_own
-        bf16x8 vf[4];
+        u32x4 vf[4];
 #pragma unroll
         for (int f = 0; f < 4; ++f)
             vf[f] = join(lds_tr(v_tr + (16 * f) * RSV), lds_tr(v_tr + (16 * f + 8) * RSV));
@@ -290,19 +295,23 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
             for (int n = 0; n < 3; ++n)
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh)
-                    o[tile_it(n)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        vf[2 * tile_jt(n) + hh], __builtin_bit_cast(bf16x8, sm.pfrag[n][hh][l]), o[tile_it(n)], 0, 0, 0);
+                    o[tile_it(n)] = E::mfma32(vf[2 * tile_jt(n) + hh], sm.pfrag[n][hh][l], o[tile_it(n)]);
 
             // store O^T: lane = token 32it + ln, registers 4q..4q+3 = columns 32w + 8q + 4g + (0..3)
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
                 const int i = 32 * it + ln;
                 if (i >= shift) {
-                    float* orow = ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
+                    const size_t ooff = (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
-                        f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
-                        *reinterpret_cast<f32x4*>(orow + 8 * qd) = val;
+                        if (kOut16) {
+                            u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
+                            *reinterpret_cast<u32x2*>(ob16 + ooff + 8 * qd) = val;
+                        } else {
+                            f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
+                            *reinterpret_cast<f32x4*>(ob + ooff + 8 * qd) = val;
+                        }
                     }
                 }
             }
@@ -310,20 +319,25 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
 
         // G4: S = gamma^L S + K^T (Gam V)
         {
-            const float gl = sm.pw[Lc];
+            if (kDecay) {
+                const float gl = sm.pw[Lc];
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) S[dt][r] *= gl;
+                    for (int r = 0; r < 16; ++r) S[dt][r] *= gl;
+            }
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
-                const f32x4 w0 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 4 * g]);
-                const f32x4 w1 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 8 + 4 * g]);
-                const bf16x8 vs = scale8(vf[f], w0, w1);
+                u32x4 vs = vf[f];
+                if (kDecay) {
+                    const f32x4 w0 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 4 * g]);
+                    const f32x4 w1 = *reinterpret_cast<const f32x4*>(&sm.gw[16 * f + 8 + 4 * g]);
+                    vs = scale8<E>(vf[f], w0, w1);
+                }
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    bf16x8 a = join(lds_tr(k_tr + (16 * f) * RSK + 32 * dt), lds_tr(k_tr + (16 * f + 8) * RSK + 32 * dt));
-                    S[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vs, S[dt], 0, 0, 0);
+                    u32x4 a = join(lds_tr(k_tr + (16 * f) * RSK + 32 * dt), lds_tr(k_tr + (16 * f + 8) * RSK + 32 * dt));
+                    S[dt] = E::mfma32(a, vs, S[dt]);
                 }
             }
         }
@@ -344,16 +358,43 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_bf16_kernel(FwdParams p) {
     }
 }
 
-hipError_t launch_fwd_bf16_states(const FwdParams& p, int BH, int D, hipStream_t stream) {
+namespace {
+
+template <int D, bool kOut, typename E, bool kOut16>
+void launch_one(const FwdParams& p, int blocks, hipStream_t stream) {
+    if (p.no_decay) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false>), dim3(blocks), dim3(D * 2), 0, stream, p);
+    else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true>), dim3(blocks), dim3(D * 2), 0, stream, p);
+}
+
+template <int D, typename E>
+void launch_elem(const FwdParams& p, int BH, bool walk, bool out16, hipStream_t stream) {
+    if (!walk) launch_one<D, false, E, false>(p, BH * (p.nseg - 1), stream);
+    else if (out16) launch_one<D, true, E, true>(p, BH * p.nseg, stream);
+    else launch_one<D, true, E, false>(p, BH * p.nseg, stream);
+}
+
+void launch_any(const FwdParams& p, int BH, int D, bool f16, bool walk, bool out16, hipStream_t stream) {
+    if (D == 64) {
+        if (f16) launch_elem<64, ElemF16>(p, BH, walk, out16, stream);
+        else launch_elem<64, ElemBf16>(p, BH, walk, out16, stream);
+    } else {
+        if (f16) launch_elem<128, ElemF16>(p, BH, walk, out16, stream);
+        else launch_elem<128, ElemBf16>(p, BH, walk, out16, stream);
+    }
+}
+
+}  // namespace
+
+// f16: the inputs are IEEE binary16 instead of bfloat16.
+hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream) {
     if (p.nseg <= 1) return hipSuccess;
-    if (D == 64) hipLaunchKernelGGL((fwd_bf16_kernel<64, false>), dim3(BH * (p.nseg - 1)), dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((fwd_bf16_kernel<128, false>), dim3(BH * (p.nseg - 1)), dim3(256), 0, stream, p);
+    launch_any(p, BH, D, f16, false, false, stream);
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_bf16_walk(const FwdParams& p, int BH, int D, hipStream_t stream) {
-    if (D == 64) hipLaunchKernelGGL((fwd_bf16_kernel<64, true>), dim3(BH * p.nseg), dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((fwd_bf16_kernel<128, true>), dim3(BH * p.nseg), dim3(256), 0, stream, p);
+// out16: p.out receives the input element type instead of fp32.
+hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream) {
+    launch_any(p, BH, D, f16, true, out16, stream);
     return hipGetLastError();
 }
 

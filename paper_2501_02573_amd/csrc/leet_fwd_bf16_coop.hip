@@ -150,7 +150,7 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     const uint16_t* qg = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
     const uint16_t* kg = reinterpret_cast<const uint16_t*>(p.k) + seq_off;
     const uint16_t* vg = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
-    float* og = p.out + seq_off;
+    float* og = static_cast<float*>(p.out) + seq_off;
 
     {
         const double gd = (double)p.gamma[h];

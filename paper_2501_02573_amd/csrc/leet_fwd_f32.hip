@@ -76,10 +76,10 @@ __global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
     const float* qb = reinterpret_cast<const float*>(p.q) + seq_off;
     const float* kb = reinterpret_cast<const float*>(p.k) + seq_off;
     const float* vb = reinterpret_cast<const float*>(p.v) + seq_off;
-    float* ob = p.out + seq_off;
+    float* ob = static_cast<float*>(p.out) + seq_off;
 
     {
-        const double gd = (double)p.gamma[h];
+        const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];
         for (int n = tid; n <= kChunk; n += NT) sm.pw[n] = (float)pow_int(gd, n);
     }
 

@@ -11,6 +11,7 @@ namespace leet {
 //     S_in(0) = state_in or 0 ;  S_in(s+1) = gamma^L S_in(s) + T_s
 // (the block recurrence of Alg. 2 with the decay of Appendix C.1, over segments).
 // One thread per four state elements; the loop over segments is sequential.
+// gamma == nullptr means gamma = 1 for every head (0/1 causal mask).
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const float* state_in,
                                                        const float* gamma, int H, int nseg,
@@ -19,7 +20,7 @@ __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const f
     if (idx >= total4) return;
     int bh = (int)(idx / DD4);
     int e4 = (int)(idx % DD4);
-    const float gl = (float)pow_int((double)gamma[bh % H], seg_tokens);
+    const float gl = gamma ? (float)pow_int((double)gamma[bh % H], seg_tokens) : 1.0f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if (state_in) acc = reinterpret_cast<const f32x4*>(state_in)[idx];
     f32x4* slot = reinterpret_cast<f32x4*>(seg_state) + (size_t)bh * (nseg - 1) * DD4 + e4;
@@ -50,12 +51,8 @@ hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float*
 // are combined with wave shuffles and one pass through LDS.
 // Thread t: columns 4*(t % (D/4)) .. +3, rows (t / (D/4)) + RP*m, RP = 1024/D.
 // ---------------------------------------------------------------------------------
-template <int D, typename T>
-__device__ __forceinline__ float load_elem(const T* p, int i);
-template <int D>
-__device__ __forceinline__ float load_elem_bf16(const uint16_t* p, int i) { return bf16_bits_to_f32(p[i]); }
-
-template <int D, bool kBf16>
+// kElem: 0 = fp32, 1 = bf16, 2 = fp16 inputs.  gamma == nullptr means gamma = 1.
+template <int D, int kElem>
 __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* k, const void* v,
                                                      const float* gamma, float* state, float* out, int H) {
     constexpr int CP = D / 4;        // threads per state row
@@ -75,17 +72,21 @@ __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* 
 
     if (tid < D) {
         size_t off = (size_t)bh * D + tid;
-        if (kBf16) {
-            sq[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(q)[off]);
-            sk[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(k)[off]);
-            sv[tid] = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(v)[off]);
+        if (kElem == 1) {
+            sq[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(q)[off]);
+            sk[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(k)[off]);
+            sv[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(v)[off]);
+        } else if (kElem == 2) {
+            sq[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(q)[off]);
+            sk[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(k)[off]);
+            sv[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(v)[off]);
         } else {
             sq[tid] = reinterpret_cast<const float*>(q)[off];
             sk[tid] = reinterpret_cast<const float*>(k)[off];
             sv[tid] = reinterpret_cast<const float*>(v)[off];
         }
     }
-    const float gm = gamma[bh % H];
+    const float gm = gamma ? gamma[bh % H] : 1.0f;
     __syncthreads();
 
     const f32x4 vv = *reinterpret_cast<const f32x4*>(&sv[4 * c4]);
@@ -117,16 +118,20 @@ __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* 
     }
 }
 
-hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
-                         float* out, int BH, int H, int D, bool bf16, hipStream_t stream) {
+template <int D>
+static void launch_decode_d(const void* q, const void* k, const void* v, const float* gamma, float* state,
+                            float* out, int BH, int H, int elem, hipStream_t stream) {
     dim3 grid(BH), block(256);
-    if (D == 64) {
-        if (bf16) hipLaunchKernelGGL((decode_kernel<64, true>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-        else hipLaunchKernelGGL((decode_kernel<64, false>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    } else {
-        if (bf16) hipLaunchKernelGGL((decode_kernel<128, true>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-        else hipLaunchKernelGGL((decode_kernel<128, false>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    }
+    if (elem == 0) hipLaunchKernelGGL((decode_kernel<D, 0>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else if (elem == 1) hipLaunchKernelGGL((decode_kernel<D, 1>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else hipLaunchKernelGGL((decode_kernel<D, 2>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+}
+
+// elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs
+hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
+                         float* out, int BH, int H, int D, int elem, hipStream_t stream) {
+    if (D == 64) launch_decode_d<64>(q, k, v, gamma, state, out, BH, H, elem, stream);
+    else launch_decode_d<128>(q, k, v, gamma, state, out, BH, H, elem, stream);
     return hipGetLastError();
 }
 

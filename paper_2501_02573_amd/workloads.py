@@ -88,7 +88,7 @@ def make_gamma(kind: str, H: int) -> torch.Tensor:
 
 
 def torch_dtype(name: str) -> torch.dtype:
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[name]
 
 
 def draw_qkv(shape: Tuple[int, ...], d: int, dtype: str, gen: torch.Generator):

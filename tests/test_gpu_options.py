@@ -1,0 +1,191 @@
+"""GPU parity for the optional forms of the path: fp16 inputs, output in the input type,
+the 0/1 causal mask (gamma = 1; Section 2.2) and multi-token decode with state hand-off.
+
+Same metric as the main parity tests: max|gpu-ref| / max|ref| per (batch, head), worst head,
+against the fp64 oracle on the same seeded inputs (the 16-bit inputs converted exactly).
+Tolerances: bf16 inputs 2e-2 and fp32 inputs 1e-4 as everywhere; fp16 inputs 2.5e-3, the bf16
+bound scaled by the three extra mantissa bits (the same intermediates -- scores, state, scaled
+V -- are rounded to the input type).  An output stored in a 16-bit type adds at most half an
+ulp of that type per element (2^-9 of the element for bf16, 2^-12 for fp16), which the same
+bounds absorb.
+"""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import elementwise_ok, max_rel_err
+from paper_2501_02573_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2.5e-3}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2501_02573_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(*ts):
+    return tuple(t.cuda() for t in ts)
+
+
+def check(got, ref, tol, what):
+    got = np.asarray(got, dtype=np.float64)
+    err = max_rel_err(got, ref)
+    say(f"  {what}: max rel err {err:.3e} (tol {tol:.1e})")
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    assert err <= tol, f"{what}: {err} > {tol}"
+    assert elementwise_ok(got, ref, tol), f"{what}: element-wise bound violated"
+
+
+def to_np(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+OPTION_SHAPES = [
+    # B, H, N, d, in dtype, 16-bit output, segments
+    (1, 2, 1, 64, "f16", False, 0),
+    (2, 3, 200, 128, "f16", False, 0),
+    (1, 4, 777, 64, "f16", True, 3),
+    (2, 2, 1025, 128, "f16", True, 4),
+    (1, 3, 333, 64, "bf16", True, 0),
+    (2, 4, 1536, 128, "bf16", True, 3),
+    (1, 2, 4096, 128, "f16", False, 0),
+]
+
+
+@pytest.mark.parametrize("shape", OPTION_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_%s_out16%d_seg%d" % s)
+def test_fp16_inputs_and_16bit_outputs(B, shape):
+    Bn, H, N, d, dtype, out16, segs = shape
+    say(f"case shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=2000 + N + d, gamma=gamma)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.1).astype(np.float32))
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    s_out = torch.empty_like(ds_in)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    odt = W.torch_dtype(dtype) if out16 else torch.float32
+
+    out = B.leet_attn_forward_v2(dq, dk, dv, dg, state_out=s_out, segments=segs, out_dtype=odt)
+    assert out.dtype == odt
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+    check(to_np(out), ref, TOL[dtype], "zero state: out")
+    check(to_np(s_out), s_ref, TOL[dtype], "zero state: final state")
+
+    out2 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, state_out=s_out, segments=segs, out_dtype=odt)
+    ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+    check(to_np(out2), ref2, TOL[dtype], "with state_in: out")
+    check(to_np(s_out), s_ref2, TOL[dtype], "with state_in: final state")
+
+    if out16:
+        # the 16-bit output is the fp32 output of the same kernel, rounded to nearest even
+        out32 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=segs)
+        assert torch.equal(out32.to(odt), out2), "16-bit output is not the rounded fp32 output"
+
+
+CAUSAL_SHAPES = [
+    (1, 2, 130, 64, "f32", 0),
+    (2, 2, 1000, 128, "f32", 3),
+    (1, 3, 777, 64, "bf16", 2),
+    (2, 4, 2048, 128, "bf16", 0),
+    (1, 2, 600, 128, "f16", 0),
+]
+
+
+@pytest.mark.parametrize("shape", CAUSAL_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_%s_seg%d" % s)
+def test_causal_mask_is_gamma_one(B, shape):
+    """The 0/1 mask: oracle run with gamma = 1; the GPU gets no gamma at all."""
+    Bn, H, N, d, dtype, segs = shape
+    say(f"case shape={shape}")
+    q, k, v, _ = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=3000 + N + d)
+    ones = torch.ones(H, dtype=torch.float32)
+    dq, dk, dv = dev(q, k, v)
+    s_out = torch.empty(Bn, H, d, d, dtype=torch.float32, device="cuda")
+    out = B.leet_attn_forward_v2(dq, dk, dv, None, state_out=s_out, segments=segs, mask=B.LEET_MASK_CAUSAL)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, ones))
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+    check(to_np(out), ref, TOL[dtype], "causal mask: out")
+    check(to_np(s_out), s_ref, TOL[dtype], "causal mask: final state")
+    # a gamma that is passed is ignored
+    junk = torch.full((H,), 0.25, dtype=torch.float32, device="cuda")
+    out_b = B.leet_attn_forward_v2(dq, dk, dv, junk, segments=segs, mask=B.LEET_MASK_CAUSAL)
+    assert torch.equal(out, out_b)
+    # and the general kernels given gamma = 1 agree to the same tolerance
+    out_c = B.leet_attn_forward_v2(dq, dk, dv, ones.cuda(), segments=segs)
+    assert max_rel_err(to_np(out_c), to_np(out)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("f16", 64), ("bf16", 128)])
+def test_decode_v2_dtypes_and_causal_mask(B, dtype, d):
+    say(f"case decode_v2 dtype={dtype} d={d}")
+    cfg = W.DecodeConfig("t", 3, 5, d, 6, 21, "pow2:1:9", dtype=dtype)
+    for mask in (B.LEET_MASK_DECAY, B.LEET_MASK_CAUSAL):
+        state0, gamma, steps = W.decode_stream(cfg)
+        g_ref = gamma if mask == B.LEET_MASK_DECAY else torch.ones_like(gamma)
+        S_ref = W.to_f64(state0); S_gpu = state0.cuda()
+        dg = gamma.cuda() if mask == B.LEET_MASK_DECAY else None
+        for q, k, v in steps:
+            o = B.leet_attn_decode_step_v2(*dev(q, k, v), dg, S_gpu, mask=mask).cpu().numpy()
+            o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), W.to_f64(g_ref), S_ref)
+            assert max_rel_err(o, o_ref) < 1e-5   # fp32 state arithmetic on exactly converted inputs
+        assert max_rel_err(S_gpu.cpu().numpy(), S_ref) < 1e-5
+
+
+@pytest.mark.parametrize("T", [2, 5, 16])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("f16", 128)])
+def test_multi_token_decode_reuses_the_chunk_kernel(B, dtype, d, T):
+    """T tokens at once with the state entering and leaving the call equal T single-token steps."""
+    Bn, H, n0 = 4, 3, 100
+    say(f"case multi-token decode dtype={dtype} d={d} T={T}")
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, n0 + T, d, dtype, seed=500 + T + d)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    S = torch.empty(Bn, H, d, d, dtype=torch.float32, device="cuda")
+    head = [t[:, :, :n0].contiguous() for t in (dq, dk, dv)]
+    tail = [t[:, :, n0:].contiguous() for t in (dq, dk, dv)]
+    B.leet_attn_forward_v2(*head, dg, state_out=S)
+    S_steps = S.clone()
+    out_T = B.leet_attn_forward_v2(*tail, dg, state_in=S, state_out=S)     # in place
+    outs = [B.leet_attn_decode_step_v2(*(t[:, :, i].contiguous() for t in tail), dg, S_steps) for i in range(T)]
+    out_steps = torch.stack(outs, dim=2)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(to_np(out_T), ref[:, :, n0:], TOL[dtype], "T tokens at once vs oracle")
+    check(to_np(out_steps), ref[:, :, n0:], TOL[dtype], "T single steps vs oracle")
+    check(to_np(S), s_ref, TOL[dtype], "state after T tokens at once")
+    check(to_np(S_steps), s_ref, TOL[dtype], "state after T single steps")
+
+
+def test_unsupported_combinations_are_rejected_and_write_nothing(B):
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 1, 64, 64, "f32", 1)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    vp = ctypes.c_void_p
+    out = torch.full((1, 1, 64, 64), 7.0, device="cuda")
+
+    def v2(in_dt, out_dt, mask, g=dg):
+        return B.lib.leet_attn_forward_v2(vp(dq.data_ptr()), vp(dk.data_ptr()), vp(dv.data_ptr()),
+                                          vp(g.data_ptr()) if g is not None else None, vp(out.data_ptr()),
+                                          None, None, None, 0, 0, 1, 1, 64, 64, in_dt, out_dt, mask, None)
+
+    assert v2(B.LEET_F32, B.LEET_BF16, B.LEET_MASK_DECAY) == B.LEET_ERR_UNSUPPORTED    # fp32 in, 16-bit out
+    assert v2(B.LEET_BF16, B.LEET_F16, B.LEET_MASK_DECAY) == B.LEET_ERR_UNSUPPORTED    # mixed 16-bit types
+    assert v2(B.LEET_F32, B.LEET_F32, 2) == B.LEET_ERR_INVALID_ARG                     # unknown mask
+    assert v2(B.LEET_F32, B.LEET_F32, B.LEET_MASK_DECAY, g=None) == B.LEET_ERR_INVALID_ARG  # decay needs gamma
+    assert v2(3, B.LEET_F32, B.LEET_MASK_DECAY) == B.LEET_ERR_UNSUPPORTED              # unknown dtype
+    # the older entry points do not take fp16
+    st = B.lib.leet_attn_forward(vp(dq.data_ptr()), vp(dk.data_ptr()), vp(dv.data_ptr()), vp(dg.data_ptr()),
+                                 vp(out.data_ptr()), 1, 1, 64, 64, B.LEET_F16, None)
+    assert st == B.LEET_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)

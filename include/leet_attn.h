@@ -133,6 +133,22 @@ int leet_attn_forward_v2(const void *q, const void *k, const void *v, const floa
                          void *workspace, size_t workspace_bytes, int segments,
                          int B, int H, int N, int d, int in_dtype, int out_dtype, int mask, void *stream);
 
+/*
+ * Row-based prefill: the same operator evaluated token by token as Alg. 1 (Appendix B.1) states
+ * it, with the discounted update of Appendix C.1 -- the decode step iterated over N with the
+ * state kept on chip.  No MFMA, sequential in N, parallel over (batch, head) and value columns
+ * only.  It is the in-library comparison point for the chunked kernels (the paper's fastest
+ * method at batch 16 is of this kind, Section 5.1); the chunked entry points are the fast path.
+ *   q, k, v    [B][H][N][d] of `dtype` (LEET_F32, LEET_BF16 or LEET_F16)
+ *   out        [B][H][N][d] float
+ *   state_in   [B][H][d][d] float or NULL;  state_out  [B][H][d][d] float or NULL (may alias)
+ *   mask       a leet_mask (gamma may be NULL for LEET_MASK_CAUSAL)
+ * Needs no workspace.
+ */
+int leet_attn_forward_recurrent(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                                const float *state_in, float *state_out,
+                                int B, int H, int N, int d, int dtype, int mask, void *stream);
+
 /* As leet_attn_decode_step_ex, with `dtype` also LEET_F16 and with a leet_mask. */
 int leet_attn_decode_step_v2(const void *q, const void *k, const void *v, const float *gamma,
                              float *state_inout, float *out, int B, int H, int d, int dtype, int mask,

@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_forward_ex",
     "leet_attn_forward_v2",
     "leet_attn_decode_step_v2",
+    "leet_attn_forward_recurrent",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
@@ -60,6 +61,8 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_forward_v2.restype = i
     lib.leet_attn_decode_step_v2.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     lib.leet_attn_decode_step_v2.restype = i
+    lib.leet_attn_forward_recurrent.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_recurrent.restype = i
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
@@ -236,6 +239,27 @@ def leet_attn_forward_v2(q, k, v, gamma: Optional[torch.Tensor], out: Optional[t
                                       ctypes.c_void_p(_stream_ptr(dev)))
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_forward_v2")
+    return out
+
+
+def leet_attn_forward_recurrent(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                                state_in: Optional[torch.Tensor] = None,
+                                state_out: Optional[torch.Tensor] = None,
+                                mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """Row-based (token-by-token) prefill on the GPU: the comparison point for the chunked path."""
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    B, H, N, d = _check_forward(q, k, v, gamma, out)
+    for name, s in (("state_in", state_in), ("state_out", state_out)):
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != (B, H, d, d)):
+            raise ValueError(f"{name} must be float32 [B, H, d, d]")
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_recurrent(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                             _ptr(state_out), B, H, N, d, _dtype_code(q), int(mask),
+                                             ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_recurrent")
     return out
 
 

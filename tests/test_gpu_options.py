@@ -189,3 +189,43 @@ def test_unsupported_combinations_are_rejected_and_write_nothing(B):
     assert st == B.LEET_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert torch.all(out == 7.0)
+
+
+# ---------------------------------------------------------------- row-based prefill (Alg. 1 on the GPU)
+RECURRENT_SHAPES = [
+    # B, H, N, d, dtype
+    (1, 1, 1, 64, "f32"),
+    (2, 3, 31, 64, "bf16"),
+    (1, 2, 32, 128, "f32"),
+    (2, 2, 33, 128, "f16"),
+    (1, 5, 777, 128, "bf16"),
+    (2, 4, 1000, 64, "f32"),
+]
+
+
+@pytest.mark.parametrize("shape", RECURRENT_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_%s" % s)
+def test_row_based_prefill_kernel(B, shape):
+    """fp32 recurrence on exactly converted inputs: far inside every input-type bound."""
+    Bn, H, N, d, dtype = shape
+    say(f"case recurrent shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=4000 + N + d, gamma=gamma)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.1).astype(np.float32))
+    dq, dk, dv, dg, ds = dev(q, k, v, gamma, s_in)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    s_out = torch.empty_like(ds)
+    out = B.leet_attn_forward_recurrent(dq, dk, dv, dg, state_out=s_out)
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+    check(to_np(out), ref, 1e-5, "zero state: out")
+    check(to_np(s_out), s_ref, 1e-5, "zero state: final state")
+    out2 = B.leet_attn_forward_recurrent(dq, dk, dv, dg, state_in=ds, state_out=ds)   # in place
+    ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+    check(to_np(out2), ref2, 1e-5, "with state_in: out")
+    check(to_np(ds), s_ref2, 1e-5, "with state_in: final state (in place)")
+    out3 = B.leet_attn_forward_recurrent(dq, dk, dv, None, mask=B.LEET_MASK_CAUSAL)
+    ref3, _ = oracle.recurrent(q64, k64, v64, np.ones(H))
+    check(to_np(out3), ref3, 1e-5, "causal mask: out")
+    # the chunked path agrees with it to the chunked path's own tolerance
+    out4 = B.leet_attn_forward_v2(dq, dk, dv, dg)
+    assert max_rel_err(to_np(out4), to_np(out)) <= TOL[dtype]

@@ -147,7 +147,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     binding.set_bf16_kernel(binding.KERNEL_COLUMN_SPLIT if args.kernel == "column-split" else binding.KERNEL_WIDE)
-    walk_name = {"wide": "fwd_bf16_kernel<128,true>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[args.kernel]
+    walk_name = {"wide": "fwd_16bit_kernel<128,true,bf16>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[args.kernel]
 
     # ---------------- headline: config 3
     cfg = W.CONFIG3
@@ -238,7 +238,7 @@ def main():
         b5 = c5.B * c5.H * (2 * c5.d * c5.d * 4 + 3 * c5.d * 2 + c5.d * 4)
         extra["decode"] = {
             "workload": c5.name, "us_per_step": ms5 * 1e3, "tokens_per_s": c5.B / (ms5 * 1e-3),
-            "roofline": {"kernel": "decode_kernel<128,true>", "bound": "hbm",
+            "roofline": {"kernel": "decode_kernel<128,bf16>", "bound": "hbm",
                          "achieved": b5 / (ms5 * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "traffic": load_traffic(c5.name, "decode"),

@@ -200,15 +200,26 @@ int leet_attn_release_workspace(void);
 /*
  * Tuning knob: which kernel a bf16 prefill uses.  Both compute the same chunked form (Alg. 2
  * with the decaying mask) and pass the same parity tests; they differ in how the work is split.
- *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns (default)
+ *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns
  *   LEET_KERNEL_COLUMN_SPLIT  d/32 workgroups per (sequence, segment), 32 value columns each,
  *                             placed on one XCD; fewer segments needed to fill the device
+ *                             (bf16 in, fp32 out, decaying mask only; other forms run wide)
+ *   LEET_KERNEL_AUTO          (default) column-split where it measured faster -- B*H*d/32 close
+ *                             to the number of compute units, N >= 1024, segments = 0 -- else wide
  * Process-wide; takes effect for calls made after it returns.  Returns LEET_ERR_INVALID_ARG for
  * any other value.
  */
-typedef enum { LEET_KERNEL_WIDE = 0, LEET_KERNEL_COLUMN_SPLIT = 1 } leet_bf16_kernel;
+typedef enum { LEET_KERNEL_WIDE = 0, LEET_KERNEL_COLUMN_SPLIT = 1, LEET_KERNEL_AUTO = 2 } leet_bf16_kernel;
 int leet_attn_set_bf16_kernel(int which);
 int leet_attn_get_bf16_kernel(void);
+
+/*
+ * What leet_attn_forward_ex would do for this shape under the current kernel choice (fp32
+ * output, decaying mask): *nseg receives the number of segments per sequence, *kernel
+ * LEET_KERNEL_WIDE or LEET_KERNEL_COLUMN_SPLIT (for fp32 and fp16 inputs always WIDE).  Either
+ * pointer may be NULL.  Host-only; touches no device.
+ */
+int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int *nseg, int *kernel);
 
 /* Static, never-NULL description of a leet_status value. */
 const char *leet_attn_strerror(int status);

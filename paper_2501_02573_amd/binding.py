@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
     "leet_attn_get_bf16_kernel",
+    "leet_attn_query_plan",
     "leet_attn_workspace_bytes",
     "leet_attn_release_workspace",
     "leet_attn_strerror",
@@ -80,6 +81,8 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_set_bf16_kernel.restype = i
     lib.leet_attn_get_bf16_kernel.argtypes = []
     lib.leet_attn_get_bf16_kernel.restype = i
+    lib.leet_attn_query_plan.argtypes = [i, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.leet_attn_query_plan.restype = i
     lib.leet_attn_strerror.argtypes = [i]
     lib.leet_attn_strerror.restype = ctypes.c_char_p
     lib.leet_attn_version.argtypes = []
@@ -132,7 +135,7 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-KERNEL_WIDE, KERNEL_COLUMN_SPLIT = 0, 1
+KERNEL_WIDE, KERNEL_COLUMN_SPLIT, KERNEL_AUTO = 0, 1, 2
 
 
 def set_bf16_kernel(which: int) -> None:
@@ -143,6 +146,15 @@ def set_bf16_kernel(which: int) -> None:
 
 def get_bf16_kernel() -> int:
     return int(lib.leet_attn_get_bf16_kernel())
+
+
+def query_plan(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0):
+    """(segments per sequence, kernel) the library would use for this shape (host-only query)."""
+    nseg, kern = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib.leet_attn_query_plan(B, H, N, d, dtype, segments, ctypes.byref(nseg), ctypes.byref(kern))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_query_plan")
+    return nseg.value, kern.value
 
 
 def workspace_bytes(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0) -> int:

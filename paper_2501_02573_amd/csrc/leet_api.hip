@@ -41,9 +41,19 @@ constexpr int kMinSegChunksBf16 = 8;
 constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 
-// Kernel choice for bf16 prefill: LEET_KERNEL_WIDE (default) or LEET_KERNEL_COLUMN_SPLIT.
-std::atomic<int> g_bf16_kernel{LEET_KERNEL_WIDE};
-bool use_coop_kernel() { return g_bf16_kernel.load(std::memory_order_relaxed) == LEET_KERNEL_COLUMN_SPLIT; }
+// Kernel choice for bf16 prefill: a leet_bf16_kernel value; LEET_KERNEL_AUTO unless the caller sets one.
+std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
+
+// LEET_KERNEL_AUTO: the column-split kernel runs when the column split alone yields about one
+// workgroup per compute unit of a 256-CU device (so no segments, no pre-pass, no scan) and the
+// sequence is long enough to amortise its three-iteration pipeline; there it measured 4 % faster
+// than the wide path (config 3: 92 vs 96.5 us).  With fewer sequences it would need segments and
+// a pre-pass of its own and loses clearly (config 4: 557 vs 378 us); with more, the wide kernel
+// needs few or no segments itself.  A caller that asks for a segment count gets the wide kernel.
+bool auto_picks_column_split(long BH, int D, int nchunks, int segments) {
+    const long wgs = BH * (D / 32);
+    return segments == 0 && wgs >= 224 && wgs <= 288 && nchunks >= 16;
+}
 
 struct Plan {
     int nseg;
@@ -55,7 +65,10 @@ struct Plan {
 // plain = fp32 output and decaying mask, the only form the column-split kernel implements
 bool make_plan(long BH, int N, int D, int dtype, bool plain, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
-    const bool coop = dtype == LEET_BF16 && plain && use_coop_kernel();
+    const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
+    const bool coop = dtype == LEET_BF16 && plain &&
+                      (choice == LEET_KERNEL_COLUMN_SPLIT ||
+                       (choice == LEET_KERNEL_AUTO && auto_picks_column_split(BH, D, nchunks, segments)));
     plan->coop = coop;
     const long per_seg = coop ? BH * (D / 32) : BH;   // workgroups one segment of every sequence gives
     const long target = coop ? kTargetWorkgroupsCoop : kTargetWorkgroupsWide;
@@ -297,6 +310,17 @@ int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, con
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
 }
 
+int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int* nseg, int* kernel) {
+    int status = LEET_OK;
+    if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    if (!shape_ok(d, dtype, &status)) return status;
+    Plan plan;
+    if (!make_plan((long)B * H, N, d, dtype, true, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (nseg) *nseg = plan.nseg;
+    if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
+    return LEET_OK;
+}
+
 int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const float* gamma,
                              float* state_inout, float* out, int B, int H, int d, int dtype, int mask,
                              void* stream) {
@@ -355,13 +379,14 @@ const char* leet_attn_strerror(int status) {
 }
 
 int leet_attn_set_bf16_kernel(int which) {
-    if (which != LEET_KERNEL_WIDE && which != LEET_KERNEL_COLUMN_SPLIT) return LEET_ERR_INVALID_ARG;
+    if (which != LEET_KERNEL_WIDE && which != LEET_KERNEL_COLUMN_SPLIT && which != LEET_KERNEL_AUTO)
+        return LEET_ERR_INVALID_ARG;
     g_bf16_kernel.store(which, std::memory_order_relaxed);
     return LEET_OK;
 }
 
 int leet_attn_get_bf16_kernel(void) { return g_bf16_kernel.load(std::memory_order_relaxed); }
 
-const char* leet_attn_version(void) { return "0.3.0"; }
+const char* leet_attn_version(void) { return "0.4.0"; }
 
 }  // extern "C"

@@ -298,20 +298,37 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
                     o[tile_it(n)] = E::mfma32(vf[2 * tile_jt(n) + hh], sm.pfrag[n][hh][l], o[tile_it(n)]);
 
             // store O^T: lane = token 32it + ln, registers 4q..4q+3 = columns 32w + 8q + 4g + (0..3)
+            if (kOut16) {
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int i = 32 * it + ln;
-                if (i >= shift) {
-                    const size_t ooff = (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
+                for (int it = 0; it < 2; ++it) {
+                    const int i = 32 * it + ln;
+                    if (i >= shift) {
+                        const size_t ooff = (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
 #pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        if (kOut16) {
+                        for (int qd = 0; qd < 4; ++qd) {
                             u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
                             *reinterpret_cast<u32x2*>(ob16 + ooff + 8 * qd) = val;
-                        } else {
-                            f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
-                            *reinterpret_cast<f32x4*>(ob + ooff + 8 * qd) = val;
                         }
+                    }
+                }
+            } else {
+                // Through a wave-private LDS tile (the V tile is dead: its fragments are in registers)
+                // so that a store instruction covers whole 128-byte row pieces: lane -> (row l/8, 16 bytes l%8).
+                float* scr = reinterpret_cast<float*>(sm.v) + w * (32 * 36);
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
+                        *reinterpret_cast<f32x4*>(scr + ln * 36 + 8 * qd + 4 * g) = val;
+                    }
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const int row = 8 * m + (l >> 3);
+                        const f32x4 val = *reinterpret_cast<const f32x4*>(scr + row * 36 + 4 * (l & 7));
+                        const int i = 32 * it + row;
+                        if (i >= shift)
+                            *reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * (l & 7)) = val;
                     }
                 }
             }

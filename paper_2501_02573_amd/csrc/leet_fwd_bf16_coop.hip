@@ -18,13 +18,26 @@
 //   waves 0..2   G1  score tile n: P^T = K rows x Q rows, decay mask, pack -> pfrag[n]
 //                    (tiles (jt,it) = (0,0), (1,1), (0,1)); after that G4 for state tile n
 //   waves 3, 4   G3  O^T[c][i] = S^T Q^T for row block it = w-3 (S^T from LDS st[c][dk]),
-//                    rows scaled by gamma^(i+1); then G2: O^T += V^T P^T (V through
-//                    transposing LDS reads, P from pfrag); store
-//   wave  5      G4  for state tile 3 (d = 128 only)
-//   waves 6, 7   staging only
+//                    rows scaled by gamma^(i+1); one iteration later G2: O^T += V^T P^T
+//                    (V through transposing LDS reads, P from pfrag); store
+//   wave  5      G4  for state tile 3 (d = 128 only); stores the finished O tiles, which the
+//                    output waves hand over through LDS, in whole 128-byte row pieces
+//   waves 6, 7   loaders: all global loads of the workgroup and the LDS writes of the tiles
 //   G4  S[dk tile][c] = gamma^L S + K^T (Gam V), A = K through transposing reads, B = the
 //       Gam-scaled V copy; the owner keeps its 32x32 fp32 tile in accumulators for the whole
 //       walk and publishes it as bf16 S^T[c][dk] for the G3 waves of the next chunk.
+//
+// A compute unit accepts only so many outstanding vector-memory requests, and a wave that
+// issues one more stalls at that instruction until there is room; a wave that both loads and
+// computes therefore spends the delivery time of its loads unable to compute.  Hence the
+// loader waves: they sit in that stall (and in the wait for the oldest register stage) while
+// the six compute waves run, and the only thing that ties the two together is one workgroup
+// barrier per chunk.  To get down to one barrier the chunk is software-pipelined: in
+// iteration t the score waves produce P(t) and S(t+1), the output waves finish chunk t-1
+// (G2 with P(t-1)) and then start chunk t (G3 with S(t)), wave 5 stores chunk t-2, and the
+// loaders write chunk t+1 to LDS and issue the loads of chunk t+3.  Q and K tiles, P fragments and S^T are
+// double-buffered in LDS, the V slice and its scaled copy triple-buffered (chunk t-1 is still
+// read in iteration t).
 //
 // MFMA conventions (32x32x16): an A (B) operand holds, in lane l, row (column) l%32 and the
 // eight contraction slots of group g = l/32; an accumulator holds, in lane l, column l%32
@@ -34,15 +47,8 @@
 // assigns key-dimension index dk = 32t + pi(m) to accumulator row m (pi swaps bits 2 and 3 of
 // m), so registers 8h..8h+7 hold eight consecutive dk and S^T is published 16 bytes at a time.
 // Outputs are accumulated transposed (lane = token): Lam is one scalar per lane and a lane
-// stores 16 contiguous bytes.
-//
-// Q, K, the V slice and its Gam-scaled copy are double-buffered in LDS: chunk t+1 is written
-// from registers while chunk t is consumed, and a ring of register stages keeps the loads of
-// three further chunks in flight; two workgroup barriers per chunk.  A ragged last chunk is
-// right-aligned in the tile (rows 64-L.. hold the tokens), which keeps every decay weight
-// chunk-independent.
-#include <type_traits>
-
+// stores 16 contiguous bytes.  A ragged last chunk is right-aligned in the tile (rows 64-L..
+// hold the tokens), which keeps every decay weight chunk-independent.
 #include "leet_common.hpp"
 
 namespace leet {
@@ -56,10 +62,11 @@ struct CoopSmem {
     static constexpr int RST = D + 8;   // S^T[c][dk]
     uint16_t q[2][kChunk * RSQ];
     uint16_t k[2][kChunk * RSQ];
-    uint16_t v[2][kChunk * RSV];
-    uint16_t vs[2][kChunk * RSV];       // Gam V: row j scaled by gamma^(63-j)
-    u32x4 pfrag[3][2][64];              // masked P^T tiles as B operands: [tile][register half][lane]
-    uint16_t st[32 * RST];
+    uint16_t v[3][kChunk * RSV];
+    uint16_t vs[3][kChunk * RSV];       // Gam V: row j scaled by gamma^(63-j)
+    u32x4 pfrag[2][3][2][64];           // masked P^T tiles as B operands: [buffer][tile][register half][lane]
+    uint16_t st[2][32 * RST];
+    float obuf[2][2][32 * 36];          // finished O tiles on their way out: [buffer][row block][row][column], padded rows
     float pw[kChunk + 4];               // gamma^n, n = 0..64
 };
 
@@ -110,12 +117,13 @@ __device__ __forceinline__ f32x16 zero16() {
 template <int D, bool kOut>
 __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngroups, int map_mode) {
     using namespace coop;
-    constexpr int NT = 512;       // threads: eight waves
-    constexpr int SL = D / 32;    // column slices (workgroups) per sequence segment
-    constexpr int DT = D / 32;    // 32-row state tiles of the slice
-    constexpr int PR = D / 8;     // 16-byte pieces per Q/K row
-    constexpr int QPT = D / 64;   // Q (and K) pieces per thread per chunk
-    constexpr int RPP = NT / PR;  // rows covered by one piece index
+    constexpr int NT = 512;        // threads: eight waves
+    constexpr int NL = 128;        // loader threads (waves 6, 7)
+    constexpr int SL = D / 32;     // column slices (workgroups) per sequence segment
+    constexpr int DT = D / 32;     // 32-row state tiles of the slice
+    constexpr int PR = D / 8;      // 16-byte pieces per Q/K row
+    constexpr int QPL = kChunk * PR / NL;  // Q (and K) pieces per loader thread per chunk
+    constexpr int RPL = NL / PR;   // rows between two pieces of one loader thread
     constexpr int RSQ = CoopSmem<D>::RSQ, RSV = CoopSmem<D>::RSV, RST = CoopSmem<D>::RST;
     __shared__ __attribute__((aligned(16))) CoopSmem<D> sm;
 
@@ -131,7 +139,8 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     const int h = bh % p.H;
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63, ln = l & 31, g = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, so the role branches are scalar
+    const int l = tid & 63, ln = l & 31, g = l >> 5;
     const int s16 = l & 15, half = (l >> 4) & 1;
     const int c0 = 32 * slice;
 
@@ -140,11 +149,15 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     const bool out_wave = kOut && (w == 3 || w == 4);            // output row block it = w - 3
     const int st_tile = (w < 3) ? w : (w == 5 ? 3 : -1);         // state tile owned (G4), if it exists
     const bool state_wave = st_tile >= 0 && st_tile < DT;
+    const bool store_wave = kOut && w == 5;                      // writes the finished O tiles to global memory
+    const bool loader = w >= 6;
     const int it_own = w - 3;
+    const int lt = tid - (NT - NL);                              // loader thread index
 
     const int tok_begin = seg * p.seg_chunks * kChunk;
     const int tok_end = (seg == p.nseg - 1) ? p.N : tok_begin + p.seg_chunks * kChunk;
-    const int nchunks = (tok_end - tok_begin + kChunk - 1) / kChunk;
+    const int n = (tok_end - tok_begin + kChunk - 1) / kChunk;   // chunks of this segment
+    const int last_shift = n * kChunk - (tok_end - tok_begin);   // empty rows at the top of the last chunk's tile
 
     const size_t seq_off = (size_t)bh * p.N * D;
     const uint16_t* qg = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
@@ -154,7 +167,7 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
 
     {
         const double gd = (double)p.gamma[h];
-        for (int n = tid; n <= kChunk; n += NT) sm.pw[n] = (float)pow_int(gd, n);
+        for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);
     }
 
     // ---- state tile of this wave: S[r] = S[dk = 32 t + pi(m(r, g))][c = c0 + ln]
@@ -175,91 +188,99 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
         }
     }
     // S^T[c][dk] in LDS: registers 8h..8h+7 are dk = 32 t + 16 h + 8 g + (0..7)
-    u32x4* st_wr = reinterpret_cast<u32x4*>(&sm.st[ln * RST + 32 * max(st_tile, 0) + 8 * g]);  // + 2h (16 elements)
-    auto publish_state = [&]() {
-        st_wr[0] = __builtin_bit_cast(u32x4, pack_half(S, 0));
-        st_wr[2] = __builtin_bit_cast(u32x4, pack_half(S, 1));
+    const int st_wr_off = ln * RST + 32 * max(st_tile, 0) + 8 * g;  // + 16 h
+    auto publish_state = [&](int buf) {
+        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off]) = __builtin_bit_cast(u32x4, pack_half(S, 0));
+        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 16]) = __builtin_bit_cast(u32x4, pack_half(S, 1));
     };
-    if (kOut && state_wave) publish_state();
+    if (kOut && state_wave) publish_state(0);
 
-    // ---- staging: thread -> pieces.  Q, K: QPT pieces of 16 bytes; V slice: one piece, fetched
-    // by both halves of the workgroup (so that every thread issues the same loads) and written
-    // to LDS by the first half.
-    const int qk_row = tid / PR, qk_cc = tid % PR;  // piece r is RPP rows further down
-    const int v_row = (tid & 255) >> 2, v_cc = tid & 3;
+    // ---- loaders: thread -> pieces.  Q, K: piece m is row m RPL + lt/PR, 16 bytes at column
+    // 8 (lt%PR); V slice: piece m is row 32 m + lt/4, 16 bytes at column c0 + 8 (lt%4).
+    const int qk_row = lt / PR, qk_cc = lt % PR;
+    const int v_row = lt >> 2, v_cc = lt & 3;
     const int qk_loff = qk_row * RSQ + qk_cc * 8;
     const int v_loff = v_row * RSV + v_cc * 8;
 
-    // Register ring of kStages chunks: chunk c travels in stage c % kStages from the moment its
-    // loads are issued (kStages chunks ahead of its use) until it is written to LDS.
+    // Two register stages: chunk c travels in stage c & 1 from the moment its loads are issued
+    // (two chunks ahead of the iteration that writes it to LDS) until it is written.  (A third
+    // stage measured no faster: the loaders are bound by the rate at which one compute unit
+    // can pull data through its vector memory path, not by latency.)
     struct Stage {
-        u32x4 q[QPT], k[QPT], v;
+        u32x4 q[QPL], k[QPL], v[2];
     };
-    constexpr int kStages = 3;
-    Stage stg[kStages];
     // Loads are unconditional (rows above a ragged chunk's first token re-read that token and
-    // are zeroed when the stage is written to LDS), so that the wait for one stage can leave
-    // the loads of the younger stages in flight.
-    auto prefetch = [&](Stage& st, int tok0) {
-        const int shift = max(0, tok0 + kChunk - tok_end);  // rows [0, shift) of the tile hold no token
-        const size_t base = (size_t)(tok0 - shift) * D;     // wave-uniform
+    // are zeroed when the stage is written to LDS; chunks past the end re-read the last one), so
+    // that the wait for one stage can leave the loads of the other in flight.
+    auto prefetch = [&](Stage& st, int c) {
+        c = min(c, n - 1);
+        const int shift = (c == n - 1) ? last_shift : 0;
+        const size_t base = (size_t)(tok_begin + c * kChunk - shift) * D;  // wave-uniform
         const uint16_t* qc = qg + base;
         const uint16_t* kc = kg + base;
         const uint16_t* vc = vg + base;
 #pragma unroll
-        for (int r = 0; r < QPT; ++r) {
-            const int row = max(qk_row + r * RPP, shift);
+        for (int m = 0; m < QPL; ++m) {
+            const int row = max(qk_row + m * RPL, shift);
             const unsigned off = (unsigned)(row * D + qk_cc * 8);
-            if (kOut) st.q[r] = *reinterpret_cast<const u32x4*>(qc + off);
-            st.k[r] = *reinterpret_cast<const u32x4*>(kc + off);
+            if (kOut) st.q[m] = *reinterpret_cast<const u32x4*>(qc + off);
+            st.k[m] = *reinterpret_cast<const u32x4*>(kc + off);
         }
-        st.v = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row, shift) * D + c0 + v_cc * 8));
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + 32 * m, shift) * D + c0 + v_cc * 8));
     };
 
-    __syncthreads();  // tables, S^T visible
+    __syncthreads();  // tables, S^T(0) visible
 
-    const float v_scale = sm.pw[kChunk - 1 - v_row];  // gamma^(63-j) for this thread's V row
-    auto store_tiles = [&](Stage& st, int buf, int tok0) {
-        const int shift = max(0, tok0 + kChunk - tok_end);
+    float v_scale[2];  // gamma^(63-j) for this loader thread's two V rows
+#pragma unroll
+    for (int m = 0; m < 2; ++m) v_scale[m] = sm.pw[kChunk - 1 - min(max(v_row, 0) + 32 * m, kChunk - 1)];
+    auto store_tiles = [&](Stage& st, int c) {
+        const int shift = (c == n - 1) ? last_shift : 0;
+        const int qb = c & 1, vb = c % 3;
         if (shift) {  // ragged last chunk: zero the rows that hold no token
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int r = 0; r < QPT; ++r)
-                if (qk_row + r * RPP < shift) {
-                    if (kOut) st.q[r] = z;
-                    st.k[r] = z;
+            for (int m = 0; m < QPL; ++m)
+                if (qk_row + m * RPL < shift) {
+                    if (kOut) st.q[m] = z;
+                    st.k[m] = z;
                 }
-            if (v_row < shift) st.v = z;
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+                if (v_row + 32 * m < shift) st.v[m] = z;
         }
 #pragma unroll
-        for (int r = 0; r < QPT; ++r) {
-            if (kOut) *reinterpret_cast<u32x4*>(&sm.q[buf][qk_loff + r * RPP * RSQ]) = st.q[r];
-            *reinterpret_cast<u32x4*>(&sm.k[buf][qk_loff + r * RPP * RSQ]) = st.k[r];
+        for (int m = 0; m < QPL; ++m) {
+            if (kOut) *reinterpret_cast<u32x4*>(&sm.q[qb][qk_loff + m * RPL * RSQ]) = st.q[m];
+            *reinterpret_cast<u32x4*>(&sm.k[qb][qk_loff + m * RPL * RSQ]) = st.k[m];
         }
-        if (tid < 256) {
-            if (kOut) *reinterpret_cast<u32x4*>(&sm.v[buf][v_loff]) = st.v;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            if (kOut) *reinterpret_cast<u32x4*>(&sm.v[vb][v_loff + 32 * m * RSV]) = st.v[m];
             typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
             u32x4 sc;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 bf16x2 pr;
-                pr[0] = (__bf16)(__uint_as_float(st.v[e] << 16) * v_scale);
-                pr[1] = (__bf16)(__uint_as_float(st.v[e] & 0xffff0000u) * v_scale);
+                pr[0] = (__bf16)(__uint_as_float(st.v[m][e] << 16) * v_scale[m]);
+                pr[1] = (__bf16)(__uint_as_float(st.v[m][e] & 0xffff0000u) * v_scale[m]);
                 sc[e] = __builtin_bit_cast(uint32_t, pr);
             }
-            *reinterpret_cast<u32x4*>(&sm.vs[buf][v_loff]) = sc;
+            *reinterpret_cast<u32x4*>(&sm.vs[vb][v_loff + 32 * m * RSV]) = sc;
         }
     };
 
-    // ---- per-lane constants
+    // ---- per-lane constants of the compute waves
     // decay weights of the score tile this wave produces: i - j = 32 (it - jt) + ln - jr
     f32x16 wgt = zero16();
     if (score_wave) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            int n = ln - (8 * (r >> 2) + 4 * g + (r & 3));
-            float diag = (n >= 0) ? sm.pw[max(n, 0)] : 0.0f;
-            wgt[r] = (w == 2) ? sm.pw[32 + n] : diag;
+            int d = ln - (8 * (r >> 2) + 4 * g + (r & 3));
+            float diag = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
+            wgt[r] = (w == 2) ? sm.pw[32 + d] : diag;
         }
     }
     const float lam_full = sm.pw[min(32 * max(it_own, 0) + ln + 1, kChunk)];  // gamma^(i+1) in a full chunk
@@ -268,45 +289,19 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     // transposing reads: lane supplies row 4g + s16/4 (+ 16 f, + 8 for the second half) and four columns
     const int tr_off_v = (4 * g + (s16 >> 2)) * RSV + 16 * half + 4 * (s16 & 3);
     const int tr_off_k = (4 * g + (s16 >> 2)) * RSQ + 32 * max(st_tile, 0) + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);
-    const uint16_t* st_rd = &sm.st[ln * RST + 8 * g];  // + 16 s
+    const int st_rd_off = ln * RST + 8 * g;  // + 16 s
 
-    // ---- the work of one chunk.  kRagged = false: a full chunk inside the steady-state loop,
-    // where every global load and store is issued unconditionally, so that the wait for the
-    // oldest register stage leaves the younger stages in flight; kRagged = true: the last,
-    // partial chunk (rows [0, shift) of the tile hold no token and are not stored).
-    auto chunk_body = [&](auto ragged_tag, int t, Stage& nxt) {
-        constexpr bool kRagged = decltype(ragged_tag)::value;
-        const int buf = t & 1;
-        const int tok0 = tok_begin + t * kChunk;
-        const int Lc = kRagged ? tok_end - tok0 : kChunk;
-        const int shift = kChunk - Lc;
+    f32x16 o = zero16();  // output waves: the row block of the chunk in progress
 
-        if (!kRagged) {
-            // chunk t+1 from its register stage into the other buffer (free since the barrier that
-            // ended chunk t-1); the stage is refilled with chunk t+1+kStages.  Past the end the
-            // last chunk is fetched again and never used.
-            store_tiles(nxt, buf ^ 1, tok_begin + min(t + 1, nchunks - 1) * kChunk);
-            prefetch(nxt, tok_begin + min(t + 1 + kStages, nchunks - 1) * kChunk);
-        }
+    // ---- iteration t of the pipeline (t = 0 .. t_end), compute waves
+    auto iteration = [&](int t) {
+        {
+            const int qb = t & 1;
+            const uint16_t* q_row = &sm.q[qb][row_off];
+            const uint16_t* k_row = &sm.k[qb][row_off];
+            const int shift = (t == n - 1) ? last_shift : 0;
 
-        const uint16_t* q_row = &sm.q[buf][row_off];
-        const uint16_t* k_row = &sm.k[buf][row_off];
-
-        // G4 math: S = gamma^L S + K^T (Gam V) for the tile this wave owns
-        auto state_update = [&]() {
-            const float gl = kRagged ? sm.pw[Lc] : gl_full;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] *= gl;
-            const uint16_t* k_tr = &sm.k[buf][tr_off_k];
-            const uint16_t* vs_tr = &sm.vs[buf][tr_off_v];
-#pragma unroll
-            for (int f = 0; f < 4; ++f)
-                S = mfma32(frag_tr(k_tr + 16 * f * RSQ, RSQ), frag_tr(vs_tr + 16 * f * RSV, RSV), S);
-        };
-
-        if (kOut) {
-            f32x16 o = zero16();
-            if (score_wave) {
+            if (score_wave && t < n) {
                 // G1: score tile n = w, (jt, it) = (0,0), (1,1), (0,1)
                 const int jt = (w == 1) ? 1 : 0, it = (w == 0) ? 0 : 1;
                 const uint16_t* ka = k_row + 32 * jt * RSQ;
@@ -316,78 +311,104 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
                 for (int s = 0; s < D / 16; ++s) acc = mfma32(frag16(ka + 16 * s), frag16(qa + 16 * s), acc);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
-                sm.pfrag[w][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
-                sm.pfrag[w][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
-            } else if (out_wave) {
-                // G3: O^T = S^T Q^T for row block it_own, rows scaled by gamma^(i+1)
-                const uint16_t* qa = q_row + 32 * it_own * RSQ;
-#pragma unroll
-                for (int s = 0; s < D / 16; ++s) o = mfma32(frag16(st_rd + 16 * s), frag16(qa + 16 * s), o);
-                const float lam = kRagged ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[r] *= lam;
-            } else if (state_wave) {
-                state_update();
+                sm.pfrag[qb][w][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
+                sm.pfrag[qb][w][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
             }
-
-            __syncthreads();  // P visible; the output waves are done reading S^T
-
-            if (score_wave) {
-                if (state_wave) {
-                    state_update();
-                    publish_state();
-                }
-            } else if (out_wave) {
-                // G2: O^T += V^T P^T over the score tiles of this row block
-                const uint16_t* v_tr = &sm.v[buf][tr_off_v];
-                if (it_own == 0) {
+            if (out_wave) {
+                if (t >= 1 && t <= n) {
+                    // finish chunk t-1: G2, O^T += V^T P^T over the score tiles of this row block; store
+                    const int pb = (t - 1) & 1;
+                    const uint16_t* v_tr = &sm.v[(t - 1) % 3][tr_off_v];
+                    if (it_own == 0) {
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh)
-                        o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[0][hh][l]), o);
-                } else {
+                        for (int hh = 0; hh < 2; ++hh)
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][0][hh][l]), o);
+                    } else {
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {
-                        o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[2][hh][l]), o);
-                        o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[1][hh][l]), o);
+                        for (int hh = 0; hh < 2; ++hh) {
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][2][hh][l]), o);
+                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][1][hh][l]), o);
+                        }
                     }
-                }
-                // store: lane = token 32 it + ln, registers 4q..4q+3 = columns c0 + 8q + 4g + (0..3)
-                const int i = 32 * it_own + ln;
-                if (!kRagged || i >= shift) {
-                    float* oc = og + (size_t)(tok0 - shift) * D;  // wave-uniform
-                    const unsigned ooff = (unsigned)(i * D + c0 + 4 * g);
+                    // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
+                    float* ot = &sm.obuf[qb][it_own][ln * 36 + 4 * g];
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
                         f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
-                        *reinterpret_cast<f32x4*>(oc + ooff + 8 * qd) = val;
+                        *reinterpret_cast<f32x4*>(ot + 8 * qd) = val;
                     }
                 }
-            } else if (state_wave) {
-                publish_state();
+                if (t < n) {
+                    // start chunk t: G3, O^T = S^T Q^T for row block it_own, rows scaled by gamma^(i+1)
+                    const uint16_t* st_rd = &sm.st[qb][st_rd_off];
+                    const uint16_t* qa = q_row + 32 * it_own * RSQ;
+                    o = zero16();
+#pragma unroll
+                    for (int s = 0; s < D / 16; ++s) o = mfma32(frag16(st_rd + 16 * s), frag16(qa + 16 * s), o);
+                    const float lam = shift ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[r] *= lam;
+                }
             }
-        } else {
-            if (state_wave) state_update();
+            if (store_wave && t >= 2) {
+                // chunk t-2, finished in iteration t-1: whole 128-byte row pieces per lane group,
+                // lane -> (row l/8 of eight rows, 16 bytes l%8)
+                const int c = t - 2;
+                const int cshift = (c == n - 1) ? last_shift : 0;
+                float* oc = og + (size_t)(tok_begin + c * kChunk - cshift) * D + c0 + 4 * (l & 7);  // + row * D
+                const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
+                    const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
+                    if (row >= cshift) *reinterpret_cast<f32x4*>(oc + (size_t)row * D) = val;
+                }
+            }
+            if (state_wave && t < n) {
+                // G4: S = gamma^L S + K^T (Gam V) for the tile this wave owns; publish S^T(t+1)
+                const float gl = shift ? sm.pw[kChunk - shift] : gl_full;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[r] *= gl;
+                const uint16_t* k_tr = &sm.k[qb][tr_off_k];
+                const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_v];
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    S = mfma32(frag_tr(k_tr + 16 * f * RSQ, RSQ), frag_tr(vs_tr + 16 * f * RSV, RSV), S);
+                if (kOut) publish_state((t + 1) & 1);
+            }
         }
-        __syncthreads();  // chunk t+1 tiles and S^T visible; P and this chunk's tiles free
+        __syncthreads();  // chunk t+1 tiles, P(t), S^T(t+1) visible; everything read in this iteration is free
     };
 
-    // ---- prologue: chunks 0..kStages-1 in flight, chunk 0 into buffer 0, its stage refilled
-    const int nfull = (tok_end - tok_begin) / kChunk;  // the steady-state loop walks the full chunks
-#pragma unroll
-    for (int c = 0; c < kStages; ++c) prefetch(stg[c], tok_begin + min(c, nchunks - 1) * kChunk);
-    store_tiles(stg[0], 0, tok_begin);
-    prefetch(stg[0], tok_begin + min(kStages, nchunks - 1) * kChunk);
-    __syncthreads();
-
-    for (int tb = 0; tb < nfull; tb += kStages) {
-#pragma unroll
-        for (int ss = 0; ss < kStages; ++ss) {
-            const int t = tb + ss;
-            if (t >= nfull) break;
-            chunk_body(std::false_type{}, t, stg[(ss + 1) % kStages]);
+    // The loaders and the compute waves run separate loops (so that the register stages are live
+    // in the loaders only) that execute the same number of workgroup barriers: one after the
+    // prologue and one per iteration t = 0 .. t_end.
+    const int t_end = kOut ? n + 1 : n - 1;  // the walk needs two more iterations to finish and store the last chunk
+    if (loader) {
+        // prologue: chunks 0 and 1 in flight, chunk 0 into its buffers, its stage refilled with chunk 2
+        Stage stg[2];
+        prefetch(stg[0], 0);
+        prefetch(stg[1], 1);
+        store_tiles(stg[0], 0);
+        prefetch(stg[0], 2);
+        __syncthreads();
+        // iteration t: chunk t+1 from its stage into LDS, the stage refilled with chunk t+3
+        auto step = [&](int t, Stage& nxt) {
+            if (t + 1 < n) {
+                store_tiles(nxt, t + 1);
+                prefetch(nxt, t + 3);
+            }
+            __syncthreads();
+        };
+        for (int t = 0; t <= t_end; t += 2) {
+            step(t, stg[1]);
+            if (t + 1 > t_end) break;
+            step(t + 1, stg[0]);
         }
+    } else {
+        __syncthreads();
+        for (int t = 0; t <= t_end; ++t) iteration(t);
     }
-    if (nfull < nchunks) chunk_body(std::true_type{}, nfull, stg[0]);
 
     // ---- hand the state on
     float* dst = nullptr;

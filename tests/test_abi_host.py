@@ -90,18 +90,32 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert ex(p, p, p, p, p, odd, None, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
 
 
-def test_kernel_choice_setter(lib):
+def test_kernel_choice_setter_and_plan_query(lib):
     from paper_2501_02573_amd import binding as b
-    assert b.get_bf16_kernel() == b.KERNEL_WIDE
-    b.set_bf16_kernel(b.KERNEL_COLUMN_SPLIT)
-    assert b.get_bf16_kernel() == b.KERNEL_COLUMN_SPLIT
-    # the column-split kernel needs fewer segments for the same number of workgroups
-    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 0
-    b.set_bf16_kernel(b.KERNEL_WIDE)
-    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 4 * 16 * 3 * 128 * 128 * 4
-    with pytest.raises(b.LeetAttnError):
-        b.set_bf16_kernel(7)
-    assert b.get_bf16_kernel() == b.KERNEL_WIDE
+    assert b.get_bf16_kernel() == b.KERNEL_AUTO
+    try:
+        # automatic choice: column split where it alone gives about one workgroup per compute unit
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # 256 workgroups
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16, 4) == (4, b.KERNEL_WIDE)          # caller asked for segments
+        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16) == (8, b.KERNEL_WIDE)            # too few sequences
+        assert b.query_plan(16, 32, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_WIDE)            # plenty of sequences
+        assert b.query_plan(4, 16, 512, 128, b.LEET_BF16)[1] == b.KERNEL_WIDE                # too short
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_F32)[1] == b.KERNEL_WIDE                # bf16 only
+        assert b.query_plan(8, 16, 4096, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # d = 64: two slices
+        assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 0
+        b.set_bf16_kernel(b.KERNEL_COLUMN_SPLIT)
+        assert b.get_bf16_kernel() == b.KERNEL_COLUMN_SPLIT
+        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16) == (2, b.KERNEL_COLUMN_SPLIT)
+        b.set_bf16_kernel(b.KERNEL_WIDE)
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)
+        assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 4 * 16 * 3 * 128 * 128 * 4
+        with pytest.raises(b.LeetAttnError):
+            b.set_bf16_kernel(7)
+        assert b.get_bf16_kernel() == b.KERNEL_WIDE
+        with pytest.raises(b.LeetAttnError):
+            b.query_plan(1, 1, 64, 96, b.LEET_BF16)
+    finally:
+        b.set_bf16_kernel(b.KERNEL_AUTO)
 
 
 def test_binding_rejects_cpu_tensors(lib):

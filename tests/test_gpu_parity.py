@@ -251,7 +251,55 @@ def test_errors_write_nothing(B):
 def column_split(B):
     B.set_bf16_kernel(B.KERNEL_COLUMN_SPLIT)
     yield B
+    B.set_bf16_kernel(B.KERNEL_AUTO)
+
+
+@pytest.fixture
+def wide_only(B):
     B.set_bf16_kernel(B.KERNEL_WIDE)
+    yield B
+    B.set_bf16_kernel(B.KERNEL_AUTO)
+
+
+def test_wide_kernel_headline_config(wide_only):
+    """The automatic choice runs the column-split kernel on config 3; the wide path must hold there too."""
+    B = wide_only
+    cfg = W.CONFIG3
+    assert B.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, B.LEET_BF16) == (4, B.KERNEL_WIDE)
+    say(f"case wide {cfg}")
+    q, k, v, gamma = W.make_forward_inputs(cfg)
+    out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out, ref, "bf16", "vs recurrent (all elements)")
+
+
+def test_automatic_kernel_choice_with_state_hand_off(B):
+    """A shape in the band where the column-split kernel is chosen: ragged length, state in and out,
+    continued by a decode step; compared with the oracle and with the wide path."""
+    Bn, H, N, d = 4, 16, 1100, 128
+    assert B.get_bf16_kernel() == B.KERNEL_AUTO
+    assert B.query_plan(Bn, H, N, d, B.LEET_BF16) == (1, B.KERNEL_COLUMN_SPLIT)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N + 1, d, "bf16", seed=31, gamma=W.make_gamma("pow2:2:9", H))
+    rng = np.random.default_rng(5)
+    # entering state of the size a steady state has (with a much larger one the fast-decaying heads'
+    # first outputs dwarf the rest of the sequence, and the per-head rms of the element-wise check
+    # no longer reflects the scale the rounding errors come from)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.02).astype(np.float32))
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    head = [t[:, :, :N].contiguous() for t in (dq, dk, dv)]
+    S = torch.empty_like(ds_in)
+    out = B.leet_attn_forward_ex(*head, dg, state_in=ds_in, state_out=S).cpu().numpy()
+    o_last = B.leet_attn_decode_step(dq[:, :, N].contiguous(), dk[:, :, N].contiguous(), dv[:, :, N].contiguous(), dg, S)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
+    check(out, ref[:, :, :N], "bf16", "automatic choice: out")
+    check(o_last.cpu().numpy()[:, :, None, :], ref[:, :, N:], "bf16", "decode step after it")
+    check(S.cpu().numpy(), s_ref, "bf16", "state after prefill + one step")
+    B.set_bf16_kernel(B.KERNEL_WIDE)
+    try:
+        out_w = B.leet_attn_forward_ex(*head, dg, state_in=ds_in).cpu().numpy()
+    finally:
+        B.set_bf16_kernel(B.KERNEL_AUTO)
+    assert max_rel_err(out_w, out) <= TOL["bf16"]
 
 
 COOP_SHAPES = [

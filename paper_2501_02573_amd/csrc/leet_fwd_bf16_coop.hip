@@ -1,6 +1,6 @@
 // Column-split chunk-walk kernel for bf16 inputs (gfx950, v_mfma_f32_32x32x16_bf16).
 //
-// Same mathematics as the wide kernel in leet_fwd_bf16.hip -- Alg. 2 (Appendix B.2) with the
+// Same mathematics as the wide kernel in leet_fwd_16bit.hip -- Alg. 2 (Appendix B.2) with the
 // decaying mask of Eq. "BCMV" (Section 2.2) and the weight split of Alg. 4 (Appendix B.3):
 //
 //     O_t     = ((Q_t K_t^T) .* D) V_t + Lam (Q_t S_t)       D[i][j] = gamma^(i-j), i >= j

@@ -15,8 +15,8 @@
 // registers).  Tokens are staged through LDS in blocks of 32, converted to fp32, with the next
 // block's global loads in flight; per token a lane reads its d/4 entries of k_i and q_i (16-byte
 // broadcast reads) and v_i[c], updates its S entries and sums its share of o_i[c]; the four row
-// groups are combined with two wave shuffles and the block's outputs leave through LDS in
-// 128-byte row pieces.
+// groups' partial sums go to LDS and are added up when the block's outputs are stored, in
+// 128-byte row pieces, so that nothing in the token loop waits on another lane.
 #include "leet_common.hpp"
 
 namespace leet {

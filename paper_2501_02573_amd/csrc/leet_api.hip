@@ -40,6 +40,7 @@ constexpr int kTargetWorkgroupsCoop = 256;
 constexpr int kMinSegChunksBf16 = 8;
 constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
+constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;  // MI355X Infinity Cache
 
 // Kernel choice for bf16 prefill: a leet_bf16_kernel value; LEET_KERNEL_AUTO unless the caller sets one.
 std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
@@ -181,6 +182,9 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     p.seg_state = static_cast<float*>(ws);
     p.H = H; p.N = N; p.nseg = plan.nseg; p.seg_chunks = plan.seg_chunks;
     p.no_decay = no_decay ? 1 : 0;
+    // Inputs that fit the 256 MB last-level cache are left to it (a pre-pass reads K and V before
+    // the walk does, and a caller's next layer may reuse them); larger ones are streamed.
+    p.stream_loads = (size_t)BH * N * d * 3 * (dtype == LEET_F32 ? 4 : 2) > kLastLevelCacheBytes ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool in16 = dtype != LEET_F32;
     const bool f16 = dtype == LEET_F16;

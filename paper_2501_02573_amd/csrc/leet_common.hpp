@@ -34,6 +34,7 @@ struct FwdParams {
     int nseg;        // segments per sequence
     int seg_chunks;  // chunks per segment (all but the last segment)
     int no_decay;    // non-zero: 0/1 causal mask, i.e. gamma = 1 for every head
+    int stream_loads;  // non-zero: q, k, v exceed the last-level cache; load them with the nontemporal hint
 };
 
 // gamma^n for integer n >= 0 in fp64 by binary exponentiation; 0^0 = 1.

@@ -105,7 +105,8 @@ __device__ __forceinline__ constexpr int tile_it(int n) { return n == 0 ? 0 : 1;
 // pre-pass: the end state of a segment started from zero).
 // E: input element type.  kOut16: O is stored in the input type instead of fp32.
 // kDecay = false: every gamma is 1, so the tables, Lam, Gam and gamma^L all drop out.
-template <int D, bool kOut, typename E, bool kOut16, bool kDecay>
+// kStream: q, k, v are loaded with the nontemporal hint (inputs larger than the last-level cache).
+template <int D, bool kOut, typename E, bool kOut16, bool kDecay, bool kStream>
 __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
     constexpr int NT = D * 2;    // threads: one wave per 32 value columns
     constexpr int NW = D / 32;   // waves
@@ -211,9 +212,15 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
             bool ok = j >= shift;
             size_t off = (size_t)(tok0 - shift + j) * D + cc * 8;
             u32x4 z = {0u, 0u, 0u, 0u};
-            if (kOut) rq[r] = ok ? *reinterpret_cast<const u32x4*>(qb + off) : z;
-            rk[r] = ok ? *reinterpret_cast<const u32x4*>(kb + off) : z;
-            rv[r] = ok ? *reinterpret_cast<const u32x4*>(vb + off) : z;
+            if (kStream) {  // inputs larger than the last-level cache: do not allocate there
+                if (kOut) rq[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + off)) : z;
+                rk[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + off)) : z;
+                rv[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + off)) : z;
+            } else {
+                if (kOut) rq[r] = ok ? *reinterpret_cast<const u32x4*>(qb + off) : z;
+                rk[r] = ok ? *reinterpret_cast<const u32x4*>(kb + off) : z;
+                rv[r] = ok ? *reinterpret_cast<const u32x4*>(vb + off) : z;
+            }
         }
     };
 
@@ -307,11 +314,13 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
 #pragma unroll
                         for (int qd = 0; qd < 4; ++qd) {
                             u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
-                            *reinterpret_cast<u32x2*>(ob16 + ooff + 8 * qd) = val;
+                            __builtin_nontemporal_store(val, reinterpret_cast<u32x2*>(ob16 + ooff + 8 * qd));
                         }
                     }
                 }
             } else {
+                // The output is written once and not read again by this library: nontemporal stores, so
+                // that it does not displace the inputs from the caches (10 % on the walk).
                 // Through a wave-private LDS tile (the V tile is dead: its fragments are in registers)
                 // so that a store instruction covers whole 128-byte row pieces: lane -> (row l/8, 16 bytes l%8).
                 float* scr = reinterpret_cast<float*>(sm.v) + w * (32 * 36);
@@ -328,7 +337,7 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
                         const f32x4 val = *reinterpret_cast<const f32x4*>(scr + row * 36 + 4 * (l & 7));
                         const int i = 32 * it + row;
                         if (i >= shift)
-                            *reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * (l & 7)) = val;
+                            __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * (l & 7)));
                     }
                 }
             }
@@ -379,8 +388,14 @@ namespace {
 
 template <int D, bool kOut, typename E, bool kOut16>
 void launch_one(const FwdParams& p, int blocks, hipStream_t stream) {
-    if (p.no_decay) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false>), dim3(blocks), dim3(D * 2), 0, stream, p);
-    else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true>), dim3(blocks), dim3(D * 2), 0, stream, p);
+    const dim3 grid(blocks), block(D * 2);
+    if (p.no_decay) {
+        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false, false>), grid, block, 0, stream, p);
+    } else {
+        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true, false>), grid, block, 0, stream, p);
+    }
 }
 
 template <int D, typename E>

@@ -352,7 +352,8 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
             }
             if (store_wave && t >= 2) {
                 // chunk t-2, finished in iteration t-1: whole 128-byte row pieces per lane group,
-                // lane -> (row l/8 of eight rows, 16 bytes l%8)
+                // lane -> (row l/8 of eight rows, 16 bytes l%8).  Nontemporal: the output is written
+                // once and must not displace Q and K, which the sibling slices re-read, from L2.
                 const int c = t - 2;
                 const int cshift = (c == n - 1) ? last_shift : 0;
                 float* oc = og + (size_t)(tok_begin + c * kChunk - cshift) * D + c0 + 4 * (l & 7);  // + row * D
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
                 for (int m = 0; m < 8; ++m) {
                     const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
                     const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                    if (row >= cshift) *reinterpret_cast<f32x4*>(oc + (size_t)row * D) = val;
+                    if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
                 }
             }
             if (state_wave && t < n) {

@@ -204,7 +204,8 @@ __global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int i = 16 * it + ln;
-                if (i >= shift) *reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 16 * w + 4 * qd) = o[it];
+                if (i >= shift)  // written once, not read again here: nontemporal
+                    __builtin_nontemporal_store(o[it], reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 16 * w + 4 * qd));
             }
         }
 

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
                 const f32x4 b = *reinterpret_cast<const f32x4*>(&so[1][vrow][vcol + e]);
                 const f32x4 cc = *reinterpret_cast<const f32x4*>(&so[2][vrow][vcol + e]);
                 const f32x4 dd = *reinterpret_cast<const f32x4*>(&so[3][vrow][vcol + e]);
-                *reinterpret_cast<f32x4*>(dst + e) = (a + b) + (cc + dd);
+                __builtin_nontemporal_store((a + b) + (cc + dd), reinterpret_cast<f32x4*>(dst + e));
             }
         }
     }

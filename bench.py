@@ -16,8 +16,10 @@ once into a HIP graph and replayed (reported for comparison, it measured no fast
 with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle (recurrent form)
 timed on this host's cores on the same workload.
 
-Defaults: 100 warm-up steps and 500 timed steps (about 60 ms of GPU work for the headline leg).
-Much shorter runs end before the device clocks have settled and read about 10 % slower.
+Defaults: 1000 warm-up steps and 1000 timed steps (about 150 ms of GPU work for the headline
+leg).  The device's clocks take on the order of 100 ms of continuous work to settle (kernel
+durations in a profiler trace fall steadily over the first several hundred launches), so much
+shorter runs read 10-25 % slower.
 """
 from __future__ import annotations
 
@@ -38,8 +40,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
     ap.add_argument("--no-graph", action="store_true", help="time plain calls only (no HIP graph replay)")
@@ -62,14 +64,18 @@ def alg_flops_forward(cfg):
 
 
 def time_eager(torch, step, steps, warmup):
+    """(host-clock ms per step, HIP-event ms per step) over exactly `steps` plain calls."""
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    e0.record()   # on the stream the library launches on (torch's current stream)
     for _ in range(steps):
         step()
+    e1.record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
+    return (time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
 def time_graph(torch, step, steps, warmup):
@@ -125,11 +131,11 @@ def prefill_leg(torch, binding, W, cfg, dev, steps, warmup, segments, use_graph)
     def step():
         binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
 
-    ms_eager = time_eager(torch, step, steps, warmup)
+    ms_eager, ms_events = time_eager(torch, step, steps, warmup)
     ms_graph = time_graph(torch, step, steps, warmup) if use_graph else None
     kms = kernel_times(binding, q, k, v, gamma, out, max(3, min(steps, 20)), segments)
     del q, k, v, out
-    return ms_eager, ms_graph, kms
+    return ms_eager, ms_graph, kms, ms_events
 
 
 def main():
@@ -155,13 +161,18 @@ def main():
     nseg3, kern3 = binding.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, binding.LEET_BF16, args.segments)
     kernel_ran = "column-split" if kern3 == binding.KERNEL_COLUMN_SPLIT else "wide"
     walk_name = {"wide": "fwd_16bit_kernel<128,true,bf16>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[kernel_ran]
-    ms_eager, ms_graph, kms = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup, args.segments,
-                                          not args.no_graph)
+    ms_eager, ms_graph, kms, ms_events = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup,
+                                                     args.segments, not args.no_graph)
     ms = ms_eager
     tokens = cfg.B * cfg.N
     nbytes = alg_bytes_forward(cfg, 2)
     nflops = alg_flops_forward(cfg)
-    walk_ms = kms[2]
+    # Duration of the dominant kernel.  With one segment the step is that one kernel, and the HIP
+    # events around the timed steps give its average launch-to-launch time in the timed region
+    # itself (an upper bound on its duration).  With segments the step is three kernels and the
+    # walk's share comes from events around repeated launches of it, taken after the timed loops.
+    single_kernel = nseg3 == 1
+    walk_ms = ms_events if single_kernel else kms[2]
     result = {
         "metric": "tokens/s, chunked decayed causal linear attention forward (B4 H16 N4096 d128 bf16)",
         "value": tokens / (ms * 1e-3),
@@ -183,7 +194,7 @@ def main():
         "tflops_algorithmic": nflops / (ms * 1e-3) / 1e12,
         "mfma_peak_frac": nflops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "hbm_frac_whole_step": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "kernel_ms": {"segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": kms[2]},
+        "kernel_ms": {"segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": walk_ms},
         "roofline": {
             "kernel": f"{walk_name} (chunk walk)",
             "bound": "hbm",
@@ -194,7 +205,11 @@ def main():
             "traffic": load_traffic(cfg.name, kernel_ran),
             "algorithmic_bytes_per_launch": nbytes,
             "avg_launch_ms": walk_ms,
+            "timed_by": ("HIP events around the timed steps (one kernel per step)" if single_kernel else
+                         "HIP events around 5 back-to-back launches, 20 times, after the timed loops"),
         },
+        "kernel_ms_isolated": {"note": "event-timed repeated launches after the timed loops",
+                               "segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": kms[2]},
     }
 
     if args.calibrate:
@@ -209,7 +224,7 @@ def main():
     if not args.no_extra:
         extra = {}
         cfg4 = W.CONFIG4
-        e4, g4, kms4 = prefill_leg(torch, binding, W, cfg4, dev, max(5, args.steps // 2), max(2, args.warmup // 2), 0,
+        e4, g4, kms4, _ = prefill_leg(torch, binding, W, cfg4, dev, max(5, args.steps // 2), max(2, args.warmup // 2), 0,
                                    not args.no_graph)
         ms4 = e4
         b4, f4 = alg_bytes_forward(cfg4, 2), alg_flops_forward(cfg4)

@@ -297,3 +297,51 @@ def test_hand_case_rejects_planted_mistakes(golden_dir):
     for name, fn in m.items():
         if name != "correct":
             assert not np.allclose(fn(g["q"], g["k"], g["v"], 0.5), g["out"]), name
+
+
+# ---------------------------------------------------------------- rank r different from the value width dv (Section 2.2)
+def _rand_rd(B, H, N, r, dv, seed):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, H, N, r))
+    k = rng.standard_normal((B, H, N, r))
+    v = rng.standard_normal((B, H, N, dv))
+    gamma = rng.uniform(0.3, 1.0, size=H)
+    return q, k, v, gamma
+
+
+@pytest.mark.parametrize("r,dv", [(3, 5), (5, 3), (4, 8)])
+def test_rank_differs_from_value_width(r, dv):
+    """B, C in R^(N x r), V in R^(N x d): pinned by library matmuls, by zero padding to the square
+    case (which the other pins hold down), and by agreement of the two forms."""
+    B, H, N = 2, 3, 37
+    q, k, v, gamma = _rand_rd(B, H, N, r, dv, seed=r * 10 + dv)
+    quad = oracle.quadratic(q, k, v, gamma)
+    rec, s_out = oracle.recurrent(q, k, v, gamma)
+    assert quad.shape == (B, H, N, dv) and s_out.shape == (B, H, r, dv)
+    # the definition by numpy routines: tril of (Q K^T) .* M, then @ V
+    i = np.arange(N)
+    for h in range(H):
+        M = np.tril(gamma[h] ** np.clip(i[:, None] - i[None, :], 0, None))
+        ref = np.matmul(np.matmul(q[:, h], np.swapaxes(k[:, h], 1, 2)) * M, v[:, h])
+        np.testing.assert_allclose(quad[:, h], ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(rec, quad, rtol=1e-11, atol=1e-12)
+    # final state = sum_j gamma^(N-1-j) k_j^T v_j
+    for h in range(H):
+        wts = gamma[h] ** (N - 1 - i)
+        ref_s = np.einsum("j,bjr,bjc->brc", wts, k[:, h], v[:, h])
+        np.testing.assert_allclose(s_out[:, h], ref_s, rtol=1e-11, atol=1e-12)
+    # zero padding to a square problem changes nothing
+    d = max(r, dv)
+    qp = np.zeros((B, H, N, d)); kp = np.zeros((B, H, N, d)); vp = np.zeros((B, H, N, d))
+    qp[..., :r] = q; kp[..., :r] = k; vp[..., :dv] = v
+    sq = oracle.quadratic(qp, kp, vp, gamma)
+    np.testing.assert_allclose(sq[..., :dv], quad, rtol=1e-13, atol=1e-13)
+    assert np.all(sq[..., dv:] == 0.0)
+    # the recurrence carries across a split, and a decode step continues it
+    n0 = 20
+    o1, s1 = oracle.recurrent(q[:, :, :n0], k[:, :, :n0], v[:, :, :n0], gamma)
+    o2, s2 = oracle.recurrent(q[:, :, n0:N - 1], k[:, :, n0:N - 1], v[:, :, n0:N - 1], gamma, state_in=s1)
+    s2 = np.ascontiguousarray(s2)
+    o3 = oracle.decode_step(q[:, :, N - 1], k[:, :, N - 1], v[:, :, N - 1], gamma, s2)
+    np.testing.assert_allclose(np.concatenate([o1, o2, o3[:, :, None]], axis=2), rec, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(s2, s_out, rtol=1e-11, atol=1e-12)

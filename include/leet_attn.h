@@ -149,6 +149,27 @@ int leet_attn_forward_recurrent(const void *q, const void *k, const void *v, con
                                 const float *state_in, float *state_out,
                                 int B, int H, int N, int d, int dtype, int mask, void *stream);
 
+/*
+ * Rank different from the value width.  The operator is defined for B, C in R^(N x r) and
+ * V in R^(N x d) (Section 2.2); the entry points above take r = d.  These take them apart:
+ *   q, k   [B][H][N][r]      v, out   [B][H][N][dv]      states   [B][H][r][dv] float
+ * Supported: r = dv in {64, 128} for every input type, and r = 128, dv = 256 (the shape of the
+ * paper's usage example, Section 4) for LEET_BF16 and LEET_F16 inputs; anything else returns
+ * LEET_ERR_UNSUPPORTED.  All other arguments as in leet_attn_forward_v2,
+ * leet_attn_forward_recurrent, leet_attn_decode_step_v2 and leet_attn_workspace_bytes.
+ */
+int leet_attn_forward_rd(const void *q, const void *k, const void *v, const float *gamma, void *out,
+                         const float *state_in, float *state_out,
+                         void *workspace, size_t workspace_bytes, int segments,
+                         int B, int H, int N, int r, int dv, int in_dtype, int out_dtype, int mask, void *stream);
+int leet_attn_forward_recurrent_rd(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                                   const float *state_in, float *state_out,
+                                   int B, int H, int N, int r, int dv, int dtype, int mask, void *stream);
+int leet_attn_decode_step_rd(const void *q, const void *k, const void *v, const float *gamma,
+                             float *state_inout, float *out, int B, int H, int r, int dv, int dtype, int mask,
+                             void *stream);
+size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtype, int segments);
+
 /* As leet_attn_decode_step_ex, with `dtype` also LEET_F16 and with a leet_mask. */
 int leet_attn_decode_step_v2(const void *q, const void *k, const void *v, const float *gamma,
                              float *state_inout, float *out, int B, int H, int d, int dtype, int mask,

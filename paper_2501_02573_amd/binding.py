@@ -29,6 +29,10 @@ EXPORTED_SYMBOLS = (
     "leet_attn_forward_v2",
     "leet_attn_decode_step_v2",
     "leet_attn_forward_recurrent",
+    "leet_attn_forward_rd",
+    "leet_attn_forward_recurrent_rd",
+    "leet_attn_decode_step_rd",
+    "leet_attn_workspace_bytes_rd",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
@@ -64,6 +68,14 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_decode_step_v2.restype = i
     lib.leet_attn_forward_recurrent.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
     lib.leet_attn_forward_recurrent.restype = i
+    lib.leet_attn_forward_rd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_rd.restype = i
+    lib.leet_attn_forward_recurrent_rd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_recurrent_rd.restype = i
+    lib.leet_attn_decode_step_rd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    lib.leet_attn_decode_step_rd.restype = i
+    lib.leet_attn_workspace_bytes_rd.argtypes = [i, i, i, i, i, i, i]
+    lib.leet_attn_workspace_bytes_rd.restype = sz
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
@@ -360,4 +372,98 @@ def leet_attn_decode_step_v2(q, k, v, gamma: Optional[torch.Tensor], state, out:
                                           B, H, d, _dtype_code(q), int(mask), ctypes.c_void_p(_stream_ptr(dev)))
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_decode_step_v2")
+    return out
+
+
+# ---------------------------------------------------------------- rank r different from the value width dv
+def workspace_bytes_rd(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments: int = 0) -> int:
+    return int(lib.leet_attn_workspace_bytes_rd(B, H, N, r, dv, dtype, segments))
+
+
+def _check_rd(q, k, v, gamma, out, any_out_dtype):
+    if q.dim() != 4 or q.shape != k.shape or v.dim() != 4 or q.shape[:3] != v.shape[:3]:
+        raise ValueError("q, k must share one [B, H, N, r] shape and v be [B, H, N, dv]")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share one dtype")
+    B, H, N, r = q.shape
+    dv = v.shape[3]
+    if gamma is not None and (gamma.dtype != torch.float32 or gamma.numel() != H):
+        raise ValueError("gamma must be float32 with one value per head")
+    if out.shape != v.shape or (out.dtype != torch.float32 and not any_out_dtype):
+        raise ValueError("out must be [B, H, N, dv]" + ("" if any_out_dtype else " float32"))
+    return B, H, N, r, dv
+
+
+def _check_states_rd(B, H, r, dv, **states):
+    for name, s in states.items():
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != (B, H, r, dv)):
+            raise ValueError(f"{name} must be float32 [B, H, r, dv]")
+
+
+def leet_attn_forward_rd(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                         state_in: Optional[torch.Tensor] = None, state_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, segments: int = 0,
+                         out_dtype: Optional[torch.dtype] = None, mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """Chunked prefill with q, k of width r and v, out of width dv; states are [B, H, r, dv]."""
+    if out is None:
+        out = torch.empty(v.shape, dtype=out_dtype or torch.float32, device=v.device)
+    B, H, N, r, dv = _check_rd(q, k, v, gamma, out, True)
+    _check_states_rd(B, H, r, dv, state_in=state_in, state_out=state_out)
+    ws_bytes = 0
+    if workspace is not None:
+        if workspace.dtype != torch.uint8:
+            raise TypeError("workspace must be a uint8 tensor")
+        ws_bytes = workspace.numel()
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out, workspace)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_rd(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                      _ptr(state_out), _ptr(workspace), ws_bytes, int(segments),
+                                      B, H, N, r, dv, _dtype_code(q), _dtype_code(out), int(mask),
+                                      ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_rd")
+    return out
+
+
+def leet_attn_forward_recurrent_rd(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                                   state_in: Optional[torch.Tensor] = None,
+                                   state_out: Optional[torch.Tensor] = None,
+                                   mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """Row-based prefill with q, k of width r and v, out of width dv."""
+    if out is None:
+        out = torch.empty(v.shape, dtype=torch.float32, device=v.device)
+    B, H, N, r, dv = _check_rd(q, k, v, gamma, out, False)
+    _check_states_rd(B, H, r, dv, state_in=state_in, state_out=state_out)
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_recurrent_rd(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                                _ptr(state_out), B, H, N, r, dv, _dtype_code(q), int(mask),
+                                                ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_recurrent_rd")
+    return out
+
+
+def leet_attn_decode_step_rd(q, k, v, gamma: Optional[torch.Tensor], state, out: Optional[torch.Tensor] = None,
+                             mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """One decode step with q, k [B, H, r], v [B, H, dv] and state [B, H, r, dv] (updated in place)."""
+    if q.dim() != 3 or q.shape != k.shape or v.dim() != 3 or q.shape[:2] != v.shape[:2]:
+        raise ValueError("q, k must share one [B, H, r] shape and v be [B, H, dv]")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share one dtype")
+    B, H, r = q.shape
+    dv = v.shape[2]
+    if out is None:
+        out = torch.empty(v.shape, dtype=torch.float32, device=v.device)
+    if gamma is not None and (gamma.dtype != torch.float32 or gamma.numel() != H):
+        raise ValueError("gamma must be float32 with one value per head")
+    _check_states_rd(B, H, r, dv, state=state)
+    if out.dtype != torch.float32 or tuple(out.shape) != (B, H, dv):
+        raise ValueError("out must be float32 [B, H, dv]")
+    dev = _check_dev(q, k, v, gamma, state, out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_decode_step_rd(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                          B, H, r, dv, _dtype_code(q), int(mask), ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_decode_step_rd")
     return out

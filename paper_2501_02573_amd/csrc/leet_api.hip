@@ -9,19 +9,19 @@
 #include "leet_common.hpp"
 
 namespace leet {
-hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream);
-hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream);
+hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
+hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_bf16_coop_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
-                           int nseg, int seg_tokens, int D, hipStream_t stream);
+                           int nseg, int seg_tokens, int D, int DV, hipStream_t stream);
 hipError_t launch_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
-                            const float* state_in, float* state_out, int BH, int H, int N, int D, int elem,
-                            hipStream_t stream);
+                            const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
+                            int elem, hipStream_t stream);
 hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
-                         float* out, int BH, int H, int D, int elem, hipStream_t stream);
+                         float* out, int BH, int H, int D, int DV, int elem, hipStream_t stream);
 }  // namespace leet
 
 namespace {
@@ -64,10 +64,11 @@ struct Plan {
 };
 
 // plain = fp32 output and decaying mask, the only form the column-split kernel implements
-bool make_plan(long BH, int N, int D, int dtype, bool plain, int segments, Plan* plan) {
+// D: width of q and k rows (rank); DV: width of v and out rows
+bool make_plan(long BH, int N, int D, int DV, int dtype, bool plain, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
     const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
-    const bool coop = dtype == LEET_BF16 && plain &&
+    const bool coop = dtype == LEET_BF16 && plain && D == DV &&
                       (choice == LEET_KERNEL_COLUMN_SPLIT ||
                        (choice == LEET_KERNEL_AUTO && auto_picks_column_split(BH, D, nchunks, segments)));
     plan->coop = coop;
@@ -89,17 +90,22 @@ bool make_plan(long BH, int N, int D, int dtype, bool plain, int segments, Plan*
     if (per_seg * (long)nseg >= (1L << 28)) return false;
     plan->nseg = nseg;
     plan->seg_chunks = seg_chunks;
-    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * D * D * sizeof(float);
+    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * D * DV * sizeof(float);
     return true;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool shape_ok(int d, int dtype, int* status) {
+// d: width of q and k rows; dv: width of v and out rows.  Square shapes for every type; rank 128 with
+// value width 256 (the shape of the paper's usage example) for the 16-bit types.
+bool shape_ok(int d, int dv, int dtype, int* status) {
     if (dtype != LEET_F32 && dtype != LEET_BF16 && dtype != LEET_F16) { *status = LEET_ERR_UNSUPPORTED; return false; }
-    if (d != 64 && d != 128) { *status = LEET_ERR_UNSUPPORTED; return false; }
+    const bool square = d == dv && (d == 64 || d == 128);
+    const bool wide_v = d == 128 && dv == 256 && dtype != LEET_F32;
+    if (!square && !wide_v) { *status = LEET_ERR_UNSUPPORTED; return false; }
     return true;
 }
+bool shape_ok(int d, int dtype, int* status) { return shape_ok(d, d, dtype, status); }
 
 // Library-owned workspace, one per device, grown on demand.
 std::mutex g_ws_mutex;
@@ -141,14 +147,14 @@ int own_workspace(int dev, size_t bytes, void** out) {
 
 int forward_impl(const void* q, const void* k, const void* v, const float* gamma, void* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
-                 int segments, int B, int H, int N, int d, int dtype, int out_dtype, int mask, void* stream,
-                 float* kernel_ms) {
+                 int segments, int B, int H, int N, int d, int dv, int dtype, int out_dtype, int mask,
+                 void* stream, float* kernel_ms) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     const bool no_decay = mask == LEET_MASK_CAUSAL;
     if (!q || !k || !v || !out || (!gamma && !no_decay)) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
-    if (!shape_ok(d, dtype, &status)) return status;
+    if (!shape_ok(d, dv, dtype, &status)) return status;
     // the output is fp32, or, for 16-bit inputs, the input type
     if (out_dtype != LEET_F32 && (out_dtype != dtype || dtype == LEET_F32)) return LEET_ERR_UNSUPPORTED;
     if (no_decay) gamma = nullptr;
@@ -160,7 +166,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dtype, out_dtype == LEET_F32 && !no_decay, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dv, dtype, out_dtype == LEET_F32 && !no_decay, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -184,7 +190,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     p.no_decay = no_decay ? 1 : 0;
     // Inputs that fit the 256 MB last-level cache are left to it (a pre-pass reads K and V before
     // the walk does, and a caller's next layer may reuse them); larger ones are streamed.
-    p.stream_loads = (size_t)BH * N * d * 3 * (dtype == LEET_F32 ? 4 : 2) > kLastLevelCacheBytes ? 1 : 0;
+    p.stream_loads = (size_t)BH * N * (2 * d + dv) * (dtype == LEET_F32 ? 4 : 2) > kLastLevelCacheBytes ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool in16 = dtype != LEET_F32;
     const bool f16 = dtype == LEET_F16;
@@ -193,15 +199,15 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     const bool coop = plan.coop;
     auto launch_states = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
-               : in16 ? leet::launch_fwd_16bit_states(p, (int)BH, d, f16, s)
+               : in16 ? leet::launch_fwd_16bit_states(p, (int)BH, d, dv, f16, s)
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
     auto launch_scan = [&]() {
-        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, s);
+        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, dv, s);
     };
     auto launch_walk = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
-               : in16 ? leet::launch_fwd_16bit_walk(p, (int)BH, d, f16, out16, s)
+               : in16 ? leet::launch_fwd_16bit_walk(p, (int)BH, d, dv, f16, out16, s)
                       : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
     };
 
@@ -253,7 +259,7 @@ extern "C" {
 int leet_attn_forward(const void* q, const void* k, const void* v, const float* gamma, float* out,
                       int B, int H, int N, int d, int dtype, void* stream) {
     if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;  // fp16 inputs go through leet_attn_forward_v2
-    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, dtype, LEET_F32,
+    return forward_impl(q, k, v, gamma, out, nullptr, nullptr, nullptr, 0, 0, B, H, N, d, d, dtype, LEET_F32,
                         LEET_MASK_DECAY, stream, nullptr);
 }
 
@@ -262,7 +268,7 @@ int leet_attn_forward_ex(const void* q, const void* k, const void* v, const floa
                          int segments, int B, int H, int N, int d, int dtype, void* stream) {
     if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, nullptr);
+                        B, H, N, d, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, nullptr);
 }
 
 int leet_attn_forward_v2(const void* q, const void* k, const void* v, const float* gamma, void* out,
@@ -270,7 +276,7 @@ int leet_attn_forward_v2(const void* q, const void* k, const void* v, const floa
                          int segments, int B, int H, int N, int d, int in_dtype, int out_dtype, int mask,
                          void* stream) {
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, in_dtype, out_dtype, mask, stream, nullptr);
+                        B, H, N, d, d, in_dtype, out_dtype, mask, stream, nullptr);
 }
 
 int leet_attn_forward_profile(const void* q, const void* k, const void* v, const float* gamma, float* out,
@@ -280,26 +286,38 @@ int leet_attn_forward_profile(const void* q, const void* k, const void* v, const
     if (!kernel_ms) return LEET_ERR_INVALID_ARG;
     if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;
     return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
-                        B, H, N, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, kernel_ms);
+                        B, H, N, d, d, dtype, LEET_F32, LEET_MASK_DECAY, stream, kernel_ms);
 }
 
-size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {
+int leet_attn_forward_rd(const void* q, const void* k, const void* v, const float* gamma, void* out,
+                         const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                         int segments, int B, int H, int N, int r, int dv, int in_dtype, int out_dtype,
+                         int mask, void* stream) {
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
+                        B, H, N, r, dv, in_dtype, out_dtype, mask, stream, nullptr);
+}
+
+size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtype, int segments) {
     int status = LEET_OK;
-    if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(d, dtype, &status)) return 0;
+    if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, dtype, true, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, r, dv, dtype, true, segments, &plan)) return 0;
     return plan.ws_bytes;
 }
 
-int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
-                                const float* state_in, float* state_out, int B, int H, int N, int d,
-                                int dtype, int mask, void* stream) {
+size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {
+    return leet_attn_workspace_bytes_rd(B, H, N, d, d, dtype, segments);
+}
+
+int leet_attn_forward_recurrent_rd(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                                   const float* state_in, float* state_out, int B, int H, int N, int d, int dv,
+                                   int dtype, int mask, void* stream) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
     if (!q || !k || !v || !out || (!gamma && mask == LEET_MASK_DECAY)) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
-    if (!shape_ok(d, dtype, &status)) return status;
+    if (!shape_ok(d, dv, dtype, &status)) return status;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
         !aligned16(state_out) || (reinterpret_cast<uintptr_t>(gamma) & 3u))
         return LEET_ERR_INVALID_ARG;
@@ -309,9 +327,16 @@ int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, con
     status = current_device(&dev);
     if (status != LEET_OK) return status;
     const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
-    hipError_t e = leet::launch_recurrent(q, k, v, gamma, out, state_in, state_out, (int)BH, H, N, d, elem,
+    hipError_t e = leet::launch_recurrent(q, k, v, gamma, out, state_in, state_out, (int)BH, H, N, d, dv, elem,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
+int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                                const float* state_in, float* state_out, int B, int H, int N, int d,
+                                int dtype, int mask, void* stream) {
+    return leet_attn_forward_recurrent_rd(q, k, v, gamma, out, state_in, state_out, B, H, N, d, d, dtype, mask,
+                                          stream);
 }
 
 int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int* nseg, int* kernel) {
@@ -319,21 +344,21 @@ int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, in
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     if (!shape_ok(d, dtype, &status)) return status;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, dtype, true, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan((long)B * H, N, d, d, dtype, true, segments, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;
     if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
     return LEET_OK;
 }
 
-int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const float* gamma,
-                             float* state_inout, float* out, int B, int H, int d, int dtype, int mask,
+int leet_attn_decode_step_rd(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dv, int dtype, int mask,
                              void* stream) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
     if (!q || !k || !v || (!gamma && mask == LEET_MASK_DECAY) || !state_inout || !out) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || d <= 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
-    if (!shape_ok(d, dtype, &status)) return status;
+    if (!shape_ok(d, dv, dtype, &status)) return status;
     if (!aligned16(state_inout) || !aligned16(out) || (reinterpret_cast<uintptr_t>(gamma) & 3u) ||
         (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
         (reinterpret_cast<uintptr_t>(v) & 3u))
@@ -344,9 +369,15 @@ int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const 
     status = current_device(&dev);
     if (status != LEET_OK) return status;
     const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
-    hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, elem,
+    hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, dv, elem,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
+int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dtype, int mask,
+                             void* stream) {
+    return leet_attn_decode_step_rd(q, k, v, gamma, state_inout, out, B, H, d, d, dtype, mask, stream);
 }
 
 int leet_attn_decode_step_ex(const void* q, const void* k, const void* v, const float* gamma,
@@ -375,7 +406,7 @@ const char* leet_attn_strerror(int status) {
     switch (status) {
         case LEET_OK: return "ok";
         case LEET_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive size, misaligned pointer or workspace too small)";
-        case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128; dtype f32, bf16 or f16; output fp32 or the 16-bit input type; device gfx950)";
+        case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128, or rank 128 with value width 256 for 16-bit inputs; dtype f32, bf16 or f16; output fp32 or the 16-bit input type; device gfx950)";
         case LEET_ERR_LAUNCH: return "HIP runtime error (launch or allocation failed)";
         case LEET_ERR_TOO_LARGE: return "sizes exceed the library's index range";
         default: return "unknown status";
@@ -391,6 +422,6 @@ int leet_attn_set_bf16_kernel(int which) {
 
 int leet_attn_get_bf16_kernel(void) { return g_bf16_kernel.load(std::memory_order_relaxed); }
 
-const char* leet_attn_version(void) { return "0.4.0"; }
+const char* leet_attn_version(void) { return "0.5.0"; }
 
 }  // extern "C"

@@ -47,11 +47,14 @@ namespace leet {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-template <int D>
+// D: rank (width of q and k rows, the paper's r); DV: width of v and out rows (the paper's d).
+template <int D, int DV>
 struct Bf16Smem {
     static constexpr int RSQ = D + 8;   // row strides (elements): 16-byte row reads of 32 rows spread over the banks
     static constexpr int RSK = D + 8;
-    static constexpr int RSV = D + 16;  // V is only read through ds_read_b64_tr_b16 (4 rows x 32 B per 16 lanes)
+    // V is only read through ds_read_b64_tr_b16 (4 rows x 32 B per 16 lanes).  Its tile doubles as
+    // the output scratch (DV/32 waves x 32 rows x 36 floats), which fixes the padding at DV = 256.
+    static constexpr int RSV = DV + (DV > 128 ? 32 : 16);
     uint16_t q[kChunk * RSQ];           // Q_t [i][dk]
     uint16_t k[kChunk * RSK];           // K_t [j][dk]
     uint16_t v[kChunk * RSV];           // V_t [j][c]
@@ -106,14 +109,18 @@ __device__ __forceinline__ constexpr int tile_it(int n) { return n == 0 ? 0 : 1;
 // E: input element type.  kOut16: O is stored in the input type instead of fp32.
 // kDecay = false: every gamma is 1, so the tables, Lam, Gam and gamma^L all drop out.
 // kStream: q, k, v are loaded with the nontemporal hint (inputs larger than the last-level cache).
-template <int D, bool kOut, typename E, bool kOut16, bool kDecay, bool kStream>
-__global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
-    constexpr int NT = D * 2;    // threads: one wave per 32 value columns
-    constexpr int NW = D / 32;   // waves
+template <int D, int DV, bool kOut, typename E, bool kOut16, bool kDecay, bool kStream>
+__global__ __launch_bounds__(DV * 2, DV > 128 ? 1 : 2) void fwd_16bit_kernel(FwdParams p) {
+    constexpr int NT = DV * 2;   // threads: one wave per 32 value columns
+    constexpr int NW = DV / 32;  // waves
     constexpr int DT = D / 32;   // 32-row tiles of the key dimension
-    constexpr int PR = D / 8;    // 16-byte pieces per row
-    constexpr int RSQ = Bf16Smem<D>::RSQ, RSK = Bf16Smem<D>::RSK, RSV = Bf16Smem<D>::RSV;
-    __shared__ __attribute__((aligned(16))) Bf16Smem<D> sm;
+    constexpr int PR = D / 8;    // 16-byte pieces per q or k row
+    constexpr int PRV = DV / 8;  // 16-byte pieces per v row
+    constexpr int QP = kChunk * PR / NT;   // q (and k) pieces per thread per chunk
+    constexpr int VP = kChunk * PRV / NT;  // v pieces per thread per chunk (= 4)
+    constexpr int RSQ = Bf16Smem<D, DV>::RSQ, RSK = Bf16Smem<D, DV>::RSK, RSV = Bf16Smem<D, DV>::RSV;
+    static_assert(kChunk * RSV * 2 >= NW * 32 * 36 * 4, "the V tile must hold the output scratch");
+    __shared__ __attribute__((aligned(16))) Bf16Smem<D, DV> sm;
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, ln = l & 31, g = l >> 5;
@@ -126,12 +133,12 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
     const int tok_end = (seg == p.nseg - 1) ? p.N : tok_begin + p.seg_chunks * kChunk;
     const int nchunks = (tok_end - tok_begin + kChunk - 1) / kChunk;
 
-    const size_t seq_off = (size_t)bh * p.N * D;
+    const size_t seq_off = (size_t)bh * p.N * D, seq_off_v = (size_t)bh * p.N * DV;
     const uint16_t* qb = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
     const uint16_t* kb = reinterpret_cast<const uint16_t*>(p.k) + seq_off;
-    const uint16_t* vb = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
-    float* ob = static_cast<float*>(p.out) + seq_off;            // kOut16 = false
-    uint16_t* ob16 = static_cast<uint16_t*>(p.out) + seq_off;    // kOut16 = true
+    const uint16_t* vb = reinterpret_cast<const uint16_t*>(p.v) + seq_off_v;
+    float* ob = static_cast<float*>(p.out) + seq_off_v;            // kOut16 = false
+    uint16_t* ob16 = static_cast<uint16_t*>(p.out) + seq_off_v;    // kOut16 = true
 
     // decay tables, fp64 -> fp32 once per workgroup
     if (kDecay) {
@@ -153,14 +160,14 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
     {
         const float* src = nullptr;
         if (kOut) {
-            if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
-            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * D;
+            if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * DV : nullptr;
+            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * DV;
         }
         if (src) {
 #pragma unroll
             for (int t = 0; t < DT; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) S[t][r] = src[dk_of(t, r) * D + c_own];
+                for (int r = 0; r < 16; ++r) S[t][r] = src[dk_of(t, r) * DV + c_own];
         } else {
 #pragma unroll
             for (int t = 0; t < DT; ++t)
@@ -202,25 +209,32 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
         lam_full[1] = kDecay ? sm.pw[32 + ln + 1] : 1.0f;
     }
 
-    u32x4 rq[4], rk[4], rv[4];
+    u32x4 rq[QP], rk[QP], rv[VP];
     auto prefetch = [&](int tok0) {
         const int shift = max(0, tok0 + kChunk - tok_end);  // rows [0, shift) of the tile stay zero
+        const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < QP; ++r) {
             int piece = r * NT + tid;
             int j = piece / PR, cc = piece % PR;
             bool ok = j >= shift;
             size_t off = (size_t)(tok0 - shift + j) * D + cc * 8;
-            u32x4 z = {0u, 0u, 0u, 0u};
             if (kStream) {  // inputs larger than the last-level cache: do not allocate there
                 if (kOut) rq[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + off)) : z;
                 rk[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + off)) : z;
-                rv[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + off)) : z;
             } else {
                 if (kOut) rq[r] = ok ? *reinterpret_cast<const u32x4*>(qb + off) : z;
                 rk[r] = ok ? *reinterpret_cast<const u32x4*>(kb + off) : z;
-                rv[r] = ok ? *reinterpret_cast<const u32x4*>(vb + off) : z;
             }
+        }
+#pragma unroll
+        for (int r = 0; r < VP; ++r) {
+            int piece = r * NT + tid;
+            int j = piece / PRV, cc = piece % PRV;
+            bool ok = j >= shift;
+            size_t off = (size_t)(tok0 - shift + j) * DV + cc * 8;
+            if (kStream) rv[r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + off)) : z;
+            else rv[r] = ok ? *reinterpret_cast<const u32x4*>(vb + off) : z;
         }
     };
 
@@ -233,11 +247,16 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
 
         if (t > 0) __syncthreads();  // everyone is done reading the previous chunk's tiles and P fragments
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < QP; ++r) {
             int piece = r * NT + tid;
             int j = piece / PR, cc = piece % PR;
             if (kOut) *reinterpret_cast<u32x4*>(&sm.q[j * RSQ + cc * 8]) = rq[r];
             *reinterpret_cast<u32x4*>(&sm.k[j * RSK + cc * 8]) = rk[r];
+        }
+#pragma unroll
+        for (int r = 0; r < VP; ++r) {
+            int piece = r * NT + tid;
+            int j = piece / PRV, cc = piece % PRV;
             *reinterpret_cast<u32x4*>(&sm.v[j * RSV + cc * 8]) = rv[r];
         }
         __syncthreads();
@@ -306,16 +325,23 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
 
             // store O^T: lane = token 32it + ln, registers 4q..4q+3 = columns 32w + 8q + 4g + (0..3)
             if (kOut16) {
+                // 16-bit output: through the same wave-private LDS tile, packed, so that a store
+                // instruction covers whole 64-byte row pieces: lane -> (row l/4, 16 bytes l%4).
+                uint32_t* scr = reinterpret_cast<uint32_t*>(sm.v) + w * (32 * 36);
 #pragma unroll
                 for (int it = 0; it < 2; ++it) {
-                    const int i = 32 * it + ln;
-                    if (i >= shift) {
-                        const size_t ooff = (size_t)(tok0 - shift + i) * D + 32 * w + 4 * g;
 #pragma unroll
-                        for (int qd = 0; qd < 4; ++qd) {
-                            u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
-                            __builtin_nontemporal_store(val, reinterpret_cast<u32x2*>(ob16 + ooff + 8 * qd));
-                        }
+                    for (int qd = 0; qd < 4; ++qd) {
+                        u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
+                        *reinterpret_cast<u32x2*>(scr + ln * 20 + 4 * qd + 2 * g) = val;
+                    }
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        const int row = 16 * m + (l >> 2);
+                        const u32x4 val = *reinterpret_cast<const u32x4*>(scr + row * 20 + 4 * (l & 3));
+                        const int i = 32 * it + row;
+                        if (i >= shift)
+                            __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(ob16 + (size_t)(tok0 - shift + i) * DV + 32 * w + 8 * (l & 3)));
                     }
                 }
             } else {
@@ -337,7 +363,7 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
                         const f32x4 val = *reinterpret_cast<const f32x4*>(scr + row * 36 + 4 * (l & 7));
                         const int i = 32 * it + row;
                         if (i >= shift)
-                            __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * D + 32 * w + 4 * (l & 7)));
+                            __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * DV + 32 * w + 4 * (l & 7)));
                     }
                 }
             }
@@ -372,61 +398,65 @@ __global__ __launch_bounds__(D * 2, 2) void fwd_16bit_kernel(FwdParams p) {
     // ---- hand the state on
     float* dst = nullptr;
     if (kOut) {
-        if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * D;
+        if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * DV;
     } else {
-        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * D;
+        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * DV;
     }
     if (dst) {
 #pragma unroll
         for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dst[dk_of(t, r) * D + c_own] = S[t][r];
+            for (int r = 0; r < 16; ++r) dst[dk_of(t, r) * DV + c_own] = S[t][r];
     }
 }
 
 namespace {
 
-template <int D, bool kOut, typename E, bool kOut16>
+template <int D, int DV, bool kOut, typename E, bool kOut16>
 void launch_one(const FwdParams& p, int blocks, hipStream_t stream) {
-    const dim3 grid(blocks), block(D * 2);
+    const dim3 grid(blocks), block(DV * 2);
     if (p.no_decay) {
-        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, false, false>), grid, block, 0, stream, p);
+        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, DV, kOut, E, kOut16, false, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_16bit_kernel<D, DV, kOut, E, kOut16, false, false>), grid, block, 0, stream, p);
     } else {
-        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((fwd_16bit_kernel<D, kOut, E, kOut16, true, false>), grid, block, 0, stream, p);
+        if (p.stream_loads) hipLaunchKernelGGL((fwd_16bit_kernel<D, DV, kOut, E, kOut16, true, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((fwd_16bit_kernel<D, DV, kOut, E, kOut16, true, false>), grid, block, 0, stream, p);
     }
 }
 
-template <int D, typename E>
+template <int D, int DV, typename E>
 void launch_elem(const FwdParams& p, int BH, bool walk, bool out16, hipStream_t stream) {
-    if (!walk) launch_one<D, false, E, false>(p, BH * (p.nseg - 1), stream);
-    else if (out16) launch_one<D, true, E, true>(p, BH * p.nseg, stream);
-    else launch_one<D, true, E, false>(p, BH * p.nseg, stream);
+    if (!walk) launch_one<D, DV, false, E, false>(p, BH * (p.nseg - 1), stream);
+    else if (out16) launch_one<D, DV, true, E, true>(p, BH * p.nseg, stream);
+    else launch_one<D, DV, true, E, false>(p, BH * p.nseg, stream);
 }
 
-void launch_any(const FwdParams& p, int BH, int D, bool f16, bool walk, bool out16, hipStream_t stream) {
+// (D, DV) is one of (64, 64), (128, 128), (128, 256); the host has checked it
+void launch_any(const FwdParams& p, int BH, int D, int DV, bool f16, bool walk, bool out16, hipStream_t stream) {
     if (D == 64) {
-        if (f16) launch_elem<64, ElemF16>(p, BH, walk, out16, stream);
-        else launch_elem<64, ElemBf16>(p, BH, walk, out16, stream);
+        if (f16) launch_elem<64, 64, ElemF16>(p, BH, walk, out16, stream);
+        else launch_elem<64, 64, ElemBf16>(p, BH, walk, out16, stream);
+    } else if (DV == 128) {
+        if (f16) launch_elem<128, 128, ElemF16>(p, BH, walk, out16, stream);
+        else launch_elem<128, 128, ElemBf16>(p, BH, walk, out16, stream);
     } else {
-        if (f16) launch_elem<128, ElemF16>(p, BH, walk, out16, stream);
-        else launch_elem<128, ElemBf16>(p, BH, walk, out16, stream);
+        if (f16) launch_elem<128, 256, ElemF16>(p, BH, walk, out16, stream);
+        else launch_elem<128, 256, ElemBf16>(p, BH, walk, out16, stream);
     }
 }
 
 }  // namespace
 
-// f16: the inputs are IEEE binary16 instead of bfloat16.
-hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream) {
+// D: width of q and k rows (rank); DV: width of v and out rows.  f16: IEEE binary16 inputs instead of bfloat16.
+hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream) {
     if (p.nseg <= 1) return hipSuccess;
-    launch_any(p, BH, D, f16, false, false, stream);
+    launch_any(p, BH, D, DV, f16, false, false, stream);
     return hipGetLastError();
 }
 
 // out16: p.out receives the input element type instead of fp32.
-hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream) {
-    launch_any(p, BH, D, f16, true, out16, stream);
+hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream) {
+    launch_any(p, BH, D, DV, f16, true, out16, stream);
     return hipGetLastError();
 }
 

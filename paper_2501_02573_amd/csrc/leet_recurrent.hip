@@ -24,11 +24,11 @@ namespace leet {
 struct RecParams {
     const void* q;          // [BH][N][D]
     const void* k;
-    const void* v;
+    const void* v;          // [BH][N][DV]
     const float* gamma;     // [H] or null (gamma = 1)
-    float* out;             // [BH][N][D] fp32
-    const float* state_in;  // [BH][D][D] or null
-    float* state_out;       // [BH][D][D] or null
+    float* out;             // [BH][N][DV] fp32
+    const float* state_in;  // [BH][D][DV] or null
+    float* state_out;       // [BH][D][DV] or null
     int H;
     int N;
 };
@@ -37,8 +37,8 @@ constexpr int kRecBlock = 32;  // tokens per staged block
 
 constexpr int kRecCols = 32;   // value columns per workgroup
 
-// kElem: 0 = fp32, 1 = bf16, 2 = fp16 inputs
-template <int D, int kElem>
+// D: width of q and k rows (rank); DV: width of v and out rows.  kElem: 0 = fp32, 1 = bf16, 2 = fp16 inputs
+template <int D, int DV, int kElem>
 __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
     constexpr int NT = 128;
     constexpr int R = D / 4;                         // state rows per lane
@@ -51,19 +51,19 @@ __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, c = l & 15, rg = l >> 4;
-    constexpr int SLICES = D / kRecCols;
+    constexpr int SLICES = DV / kRecCols;
     const int bh = blockIdx.x / SLICES;
     const int c0 = (blockIdx.x % SLICES) * kRecCols;
     const int cl = 16 * w + c;                       // column within the slice
     const float gm = p.gamma ? p.gamma[bh % p.H] : 1.0f;
-    const size_t seq_off = (size_t)bh * p.N * D;
-    float* ob = p.out + seq_off;
+    const size_t seq_off = (size_t)bh * p.N * D, seq_off_v = (size_t)bh * p.N * DV;
+    float* ob = p.out + seq_off_v;
 
     float S[R];
     {
-        const float* src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
+        const float* src = p.state_in ? p.state_in + (size_t)bh * D * DV : nullptr;
 #pragma unroll
-        for (int e = 0; e < R; ++e) S[e] = src ? src[(size_t)(rg * R + e) * D + c0 + cl] : 0.0f;
+        for (int e = 0; e < R; ++e) S[e] = src ? src[(size_t)(rg * R + e) * DV + c0 + cl] : 0.0f;
     }
 
     // eight consecutive elements of a tensor, converted to fp32 (zeros past the end of the sequence)
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
             fetch8(p.q, off, ok, rq[m]);
             fetch8(p.k, off, ok, rk[m]);
         }
-        fetch8(p.v, seq_off + (size_t)(tok0 + vrow) * D + c0 + vcol, tok0 + vrow < p.N, rv);
+        fetch8(p.v, seq_off_v + (size_t)(tok0 + vrow) * DV + c0 + vcol, tok0 + vrow < p.N, rv);
     };
 
     prefetch(0);
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
         __syncthreads();
         // the four row groups are summed on the way out
         if (vrow < nt) {
-            float* dst = ob + (size_t)(tok0 + vrow) * D + c0 + vcol;
+            float* dst = ob + (size_t)(tok0 + vrow) * DV + c0 + vcol;
 #pragma unroll
             for (int e = 0; e < 8; e += 4) {
                 const f32x4 a = *reinterpret_cast<const f32x4*>(&so[0][vrow][vcol + e]);
@@ -154,29 +154,31 @@ __global__ __launch_bounds__(128) void recurrent_kernel(RecParams p) {
     }
 
     if (p.state_out) {
-        float* dst = p.state_out + (size_t)bh * D * D;
+        float* dst = p.state_out + (size_t)bh * D * DV;
 #pragma unroll
-        for (int e = 0; e < R; ++e) dst[(size_t)(rg * R + e) * D + c0 + cl] = S[e];
+        for (int e = 0; e < R; ++e) dst[(size_t)(rg * R + e) * DV + c0 + cl] = S[e];
     }
 }
 
-template <int D>
+template <int D, int DV>
 static void launch_recurrent_d(const RecParams& p, int BH, int elem, hipStream_t stream) {
-    dim3 grid(BH * (D / kRecCols)), block(128);
-    if (elem == 0) hipLaunchKernelGGL((recurrent_kernel<D, 0>), grid, block, 0, stream, p);
-    else if (elem == 1) hipLaunchKernelGGL((recurrent_kernel<D, 1>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((recurrent_kernel<D, 2>), grid, block, 0, stream, p);
+    dim3 grid(BH * (DV / kRecCols)), block(128);
+    if (elem == 0) hipLaunchKernelGGL((recurrent_kernel<D, DV, 0>), grid, block, 0, stream, p);
+    else if (elem == 1) hipLaunchKernelGGL((recurrent_kernel<D, DV, 1>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((recurrent_kernel<D, DV, 2>), grid, block, 0, stream, p);
 }
 
-// elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs; gamma null means gamma = 1
+// elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs; gamma null means gamma = 1;
+// (D, DV) one of (64, 64), (128, 128), (128, 256)
 hipError_t launch_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
-                            const float* state_in, float* state_out, int BH, int H, int N, int D, int elem,
-                            hipStream_t stream) {
+                            const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
+                            int elem, hipStream_t stream) {
     RecParams p;
     p.q = q; p.k = k; p.v = v; p.gamma = gamma; p.out = out;
     p.state_in = state_in; p.state_out = state_out; p.H = H; p.N = N;
-    if (D == 64) launch_recurrent_d<64>(p, BH, elem, stream);
-    else launch_recurrent_d<128>(p, BH, elem, stream);
+    if (D == 64) launch_recurrent_d<64, 64>(p, BH, elem, stream);
+    else if (DV == 128) launch_recurrent_d<128, 128>(p, BH, elem, stream);
+    else launch_recurrent_d<128, 256>(p, BH, elem, stream);
     return hipGetLastError();
 }
 

@@ -31,10 +31,11 @@ __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const f
     }
 }
 
+// D x DV: shape of one state (rank x value width)
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
-                           int nseg, int seg_tokens, int D, hipStream_t stream) {
+                           int nseg, int seg_tokens, int D, int DV, hipStream_t stream) {
     if (nseg <= 1) return hipSuccess;
-    int DD4 = D * D / 4;
+    int DD4 = D * DV / 4;
     size_t total4 = (size_t)BH * DD4;
     unsigned blocks = (unsigned)((total4 + 255) / 256);
     hipLaunchKernelGGL(seg_scan_kernel, dim3(blocks), dim3(256), 0, stream, seg_state, state_in, gamma, H,
@@ -44,48 +45,43 @@ hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float*
 
 // ---------------------------------------------------------------------------------
 // Decode step (Alg. 1, Appendix B.1, with the discounted update of Appendix C.1):
-//     S <- gamma S + k^T v ;  o = q S        per (batch, head), S is D x D fp32.
+//     S <- gamma S + k^T v ;  o = q S        per (batch, head), S is D x DV fp32
+// (D = width of q and k, DV = width of v and o; D = DV except for rank 128 / width 256).
 // One workgroup of 256 threads streams one state once: every thread issues all of
-// its 16-byte loads up front (D*D*4/256/16 of them), updates in registers, stores
+// its 16-byte loads up front (D*DV*4/256/16 of them), updates in registers, stores
 // back to the same addresses and accumulates its share of o = q S; the partial sums
 // are combined with wave shuffles and one pass through LDS.
-// Thread t: columns 4*(t % (D/4)) .. +3, rows (t / (D/4)) + RP*m, RP = 1024/D.
+// Thread t: columns 4*(t % (DV/4)) .. +3, rows (t / (DV/4)) + RP*m, RP = 1024/DV.
 // ---------------------------------------------------------------------------------
 // kElem: 0 = fp32, 1 = bf16, 2 = fp16 inputs.  gamma == nullptr means gamma = 1.
-template <int D, int kElem>
+template <int D, int DV, int kElem>
 __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* k, const void* v,
                                                      const float* gamma, float* state, float* out, int H) {
-    constexpr int CP = D / 4;        // threads per state row
+    constexpr int CP = DV / 4;       // threads per state row
     constexpr int RP = 256 / CP;     // rows per pass
     constexpr int NPASS = D / RP;    // passes (= 16-byte loads per thread)
-    __shared__ float sq[D], sk[D], sv[D];
+    __shared__ float sq[D], sk[D], sv[DV];
     __shared__ f32x4 red[4][CP];
 
     const int tid = threadIdx.x;
     const int bh = blockIdx.x;
     const int c4 = tid % CP, r0 = tid / CP;
-    f32x4* Sg = reinterpret_cast<f32x4*>(state + (size_t)bh * D * D);
+    f32x4* Sg = reinterpret_cast<f32x4*>(state + (size_t)bh * D * DV);
 
     f32x4 s[NPASS];
 #pragma unroll
     for (int m = 0; m < NPASS; ++m) s[m] = Sg[(size_t)(r0 + RP * m) * CP + c4];
 
+    auto elem = [&](const void* base, size_t off) -> float {
+        if (kElem == 1) return ElemBf16::lo(reinterpret_cast<const uint16_t*>(base)[off]);
+        if (kElem == 2) return ElemF16::lo(reinterpret_cast<const uint16_t*>(base)[off]);
+        return reinterpret_cast<const float*>(base)[off];
+    };
     if (tid < D) {
-        size_t off = (size_t)bh * D + tid;
-        if (kElem == 1) {
-            sq[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(q)[off]);
-            sk[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(k)[off]);
-            sv[tid] = ElemBf16::lo(reinterpret_cast<const uint16_t*>(v)[off]);
-        } else if (kElem == 2) {
-            sq[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(q)[off]);
-            sk[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(k)[off]);
-            sv[tid] = ElemF16::lo(reinterpret_cast<const uint16_t*>(v)[off]);
-        } else {
-            sq[tid] = reinterpret_cast<const float*>(q)[off];
-            sk[tid] = reinterpret_cast<const float*>(k)[off];
-            sv[tid] = reinterpret_cast<const float*>(v)[off];
-        }
+        sq[tid] = elem(q, (size_t)bh * D + tid);
+        sk[tid] = elem(k, (size_t)bh * D + tid);
     }
+    if (tid < DV) sv[tid] = elem(v, (size_t)bh * DV + tid);
     const float gm = gamma ? gamma[bh % H] : 1.0f;
     __syncthreads();
 
@@ -114,24 +110,25 @@ __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* 
     __syncthreads();
     if (tid < CP) {
         f32x4 r = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
-        reinterpret_cast<f32x4*>(out + (size_t)bh * D)[tid] = r;
+        reinterpret_cast<f32x4*>(out + (size_t)bh * DV)[tid] = r;
     }
 }
 
-template <int D>
+template <int D, int DV>
 static void launch_decode_d(const void* q, const void* k, const void* v, const float* gamma, float* state,
                             float* out, int BH, int H, int elem, hipStream_t stream) {
     dim3 grid(BH), block(256);
-    if (elem == 0) hipLaunchKernelGGL((decode_kernel<D, 0>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    else if (elem == 1) hipLaunchKernelGGL((decode_kernel<D, 1>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    else hipLaunchKernelGGL((decode_kernel<D, 2>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    if (elem == 0) hipLaunchKernelGGL((decode_kernel<D, DV, 0>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else if (elem == 1) hipLaunchKernelGGL((decode_kernel<D, DV, 1>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else hipLaunchKernelGGL((decode_kernel<D, DV, 2>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
 }
 
-// elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs
+// elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs; (D, DV) one of (64, 64), (128, 128), (128, 256)
 hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
-                         float* out, int BH, int H, int D, int elem, hipStream_t stream) {
-    if (D == 64) launch_decode_d<64>(q, k, v, gamma, state, out, BH, H, elem, stream);
-    else launch_decode_d<128>(q, k, v, gamma, state, out, BH, H, elem, stream);
+                         float* out, int BH, int H, int D, int DV, int elem, hipStream_t stream) {
+    if (D == 64) launch_decode_d<64, 64>(q, k, v, gamma, state, out, BH, H, elem, stream);
+    else if (DV == 128) launch_decode_d<128, 128>(q, k, v, gamma, state, out, BH, H, elem, stream);
+    else launch_decode_d<128, 256>(q, k, v, gamma, state, out, BH, H, elem, stream);
     return hipGetLastError();
 }
 

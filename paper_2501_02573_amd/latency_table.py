@@ -12,6 +12,7 @@ Rows are this library's methods:
                                lightningAttention-2 rows play), fp32 output
   chunked bf16, bf16 out       the same with 16-bit output
   row-based bf16               the token-by-token recursion (the role of causal-dot-product)
+  chunked bf16, dim 256        rank 128 with value width 256, the shape of the paper's usage example
 The paper's own lightningAttention-2 row (one A6000; other hardware, so context only) is printed
 underneath the tables with the decaying mask.
 
@@ -41,12 +42,15 @@ def _methods(torch, binding):
     bf16, f16, f32 = torch.bfloat16, torch.float16, torch.float32
     fwd = binding.leet_attn_forward_v2
     rec = binding.leet_attn_forward_recurrent
+    frd = binding.leet_attn_forward_rd
+    # (name, input dtype, output dtype, value width, call)
     return (
-        ("chunked bf16", bf16, f32, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
-        ("chunked fp16", f16, f32, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
-        ("chunked fp32", f32, f32, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
-        ("chunked bf16, bf16 out", bf16, bf16, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
-        ("row-based bf16", bf16, f32, lambda q, k, v, g, o, m: rec(q, k, v, g, out=o, mask=m)),
+        ("chunked bf16", bf16, f32, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
+        ("chunked fp16", f16, f32, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
+        ("chunked fp32", f32, f32, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
+        ("chunked bf16, bf16 out", bf16, bf16, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
+        ("row-based bf16", bf16, f32, DIM, lambda q, k, v, g, o, m: rec(q, k, v, g, out=o, mask=m)),
+        ("chunked bf16, dim 256", bf16, f32, 2 * DIM, lambda q, k, v, g, o, m: frd(q, k, v, g, out=o, mask=m)),
     )
 
 
@@ -80,7 +84,7 @@ def run(out_path=None, n_list=N_LIST, batches=(1, 16), reps=REPS, max_bytes=200e
     lines = [
         "# Single-layer latency versus sequence length (seconds, mean ± std of %d runs)" % reps,
         "",
-        "MI355X, one GPU; shape [batch, %d, N, %d], rank = dim = %d; synthetic q, k, v ~ N(0,1)/sqrt(d);"
+        "MI355X, one GPU; shape [batch, %d, N, %d], rank = dim = %d (last row: dim 256); synthetic q, k, v ~ N(0,1)/sqrt(d);"
         % (HEADS, DIM, DIM),
         "per-head gamma = 1 - 2^-(5 + 5h/31).  Layout and protocol follow the paper's single-layer tables",
         "(Section 5.1), whose heads, dimensions and dtype are not stated.",
@@ -96,20 +100,21 @@ def run(out_path=None, n_list=N_LIST, batches=(1, 16), reps=REPS, max_bytes=200e
             rows = {name: [] for name, *_ in _methods(torch, binding)}
             for n in n_list:
                 shape = (batch, HEADS, n, DIM)
-                numel = batch * HEADS * n * DIM
+                rows_n = batch * HEADS * n
                 cache = {}
-                for name, in_dt, out_dt, fn in _methods(torch, binding):
-                    need = numel * (3 * torch.empty((), dtype=in_dt).element_size()
-                                    + torch.empty((), dtype=out_dt).element_size())
+                for name, in_dt, out_dt, dv, fn in _methods(torch, binding):
+                    isz, osz = torch.empty((), dtype=in_dt).element_size(), torch.empty((), dtype=out_dt).element_size()
+                    need = rows_n * ((2 * DIM + dv) * isz + dv * osz)
                     if need > max_bytes:
                         rows[name].append("too large")
                         continue
-                    if in_dt not in cache:
+                    if (in_dt, dv) not in cache:
                         cache.clear()
-                        cache[in_dt] = tuple(torch.randn(shape, device=dev, generator=gen, dtype=in_dt).mul_(DIM ** -0.5)
-                                             for _ in range(3))
-                    q, k, v = cache[in_dt]
-                    out = torch.empty(shape, dtype=out_dt, device=dev)
+                        cache[(in_dt, dv)] = tuple(
+                            torch.randn(shape[:3] + (w,), device=dev, generator=gen, dtype=in_dt).mul_(w ** -0.5)
+                            for w in (DIM, DIM, dv))
+                    q, k, v = cache[(in_dt, dv)]
+                    out = torch.empty(v.shape, dtype=out_dt, device=dev)
                     mean, std = _time_one(torch, lambda: fn(q, k, v, gamma, out, mask), reps)
                     rows[name].append("%.3g ± %.1g" % (mean, std))
                     print("  N=%d %s: %.3g s" % (n, name, mean), flush=True)

@@ -119,6 +119,18 @@ def make_custom_forward_inputs(B: int, H: int, N: int, d: int, dtype: str, seed:
     return q, k, v, gamma.to(torch.float32)
 
 
+def make_rd_forward_inputs(B: int, H: int, N: int, r: int, dv: int, dtype: str, seed: int,
+                           gamma: Optional[torch.Tensor] = None):
+    """Rank r different from the value width dv: q, k ~ N(0,1)/sqrt(r) [B,H,N,r], v ~ N(0,1)/sqrt(dv) [B,H,N,dv]."""
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    q = (torch.randn((B, H, N, r), generator=gen, dtype=torch.float32) * float(r) ** -0.5).to(torch_dtype(dtype))
+    k = (torch.randn((B, H, N, r), generator=gen, dtype=torch.float32) * float(r) ** -0.5).to(torch_dtype(dtype))
+    v = (torch.randn((B, H, N, dv), generator=gen, dtype=torch.float32) * float(dv) ** -0.5).to(torch_dtype(dtype))
+    if gamma is None:
+        gamma = make_gamma("pow2:3:9", H) if H > 1 else make_gamma("scalar:0.9", 1)
+    return q, k, v, gamma.to(torch.float32)
+
+
 def make_decode_state(cfg: DecodeConfig, gen: torch.Generator) -> torch.Tensor:
     """Initial state S[B, H, d, d] fp32 ~ N(0, sigma^2) (variance 0.01)."""
     s = torch.randn((cfg.B, cfg.H, cfg.d, cfg.d), generator=gen, dtype=torch.float32)

@@ -229,3 +229,63 @@ def test_row_based_prefill_kernel(B, shape):
     # the chunked path agrees with it to the chunked path's own tolerance
     out4 = B.leet_attn_forward_v2(dq, dk, dv, dg)
     assert max_rel_err(to_np(out4), to_np(out)) <= TOL[dtype]
+
+
+# ---------------------------------------------------------------- rank 128, value width 256 (the paper's usage example)
+RD_SHAPES = [
+    # B, H, N, dtype, 16-bit output, segments
+    (1, 2, 1, "bf16", False, 0),
+    (2, 3, 200, "bf16", False, 0),
+    (1, 4, 777, "f16", False, 3),
+    (2, 2, 1025, "bf16", True, 4),
+    (1, 3, 2048, "f16", True, 0),
+]
+
+
+@pytest.mark.parametrize("shape", RD_SHAPES, ids=lambda s: "B%d_H%d_N%d_%s_out16%d_seg%d" % s)
+def test_rank_128_value_width_256(B, shape):
+    Bn, H, N, dtype, out16, segs = shape
+    r, dv = 128, 256
+    say(f"case r={r} dv={dv} shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N + 1, r, dv, dtype, seed=5000 + N, gamma=gamma)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, r, dv)) * 0.05).astype(np.float32))
+    dq, dk, dv_, dg, ds_in = dev(q, k, v, gamma, s_in)
+    head = [t[:, :, :N].contiguous() for t in (dq, dk, dv_)]
+    odt = W.torch_dtype(dtype) if out16 else torch.float32
+    S = torch.empty_like(ds_in)
+    ws = torch.empty(max(B.workspace_bytes_rd(Bn, H, N, r, dv, B.LEET_BF16 if dtype == "bf16" else B.LEET_F16, segs), 1),
+                     dtype=torch.uint8, device="cuda")
+    out = B.leet_attn_forward_rd(*head, dg, state_in=ds_in, state_out=S, workspace=ws, segments=segs, out_dtype=odt)
+    o_last = B.leet_attn_decode_step_rd(dq[:, :, N].contiguous(), dk[:, :, N].contiguous(), dv_[:, :, N].contiguous(), dg, S)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
+    assert out.shape == (Bn, H, N, dv) and out.dtype == odt
+    check(to_np(out), ref[:, :, :N], TOL[dtype], "chunked: out")
+    check(to_np(o_last)[:, :, None, :], ref[:, :, N:], TOL[dtype], "decode step after it")
+    check(to_np(S), s_ref, TOL[dtype], "state after prefill + one step")
+    # the row-based kernel on the same inputs: fp32 recurrence, far tighter
+    S2 = torch.empty_like(ds_in)
+    out_r = B.leet_attn_forward_recurrent_rd(dq, dk, dv_, dg, state_in=ds_in, state_out=S2)
+    check(to_np(out_r), ref, 1e-5, "row-based: out")
+    check(to_np(S2), s_ref, 1e-5, "row-based: final state")
+    # 0/1 mask
+    out_c = B.leet_attn_forward_rd(*head, None, segments=segs, mask=B.LEET_MASK_CAUSAL)
+    ref_c, _ = oracle.recurrent(*(W.to_f64(t)[:, :, :N] for t in (q, k, v)), np.ones(H))
+    check(to_np(out_c), ref_c, TOL[dtype], "causal mask: out")
+
+
+def test_rank_value_width_combinations_rejected(B):
+    q = torch.zeros(1, 1, 64, 128, device="cuda", dtype=torch.float32)
+    v = torch.zeros(1, 1, 64, 256, device="cuda", dtype=torch.float32)
+    g = torch.ones(1, device="cuda")
+    with pytest.raises(B.LeetAttnError) as ei:        # fp32 inputs: square shapes only
+        B.leet_attn_forward_rd(q, q, v, g)
+    assert ei.value.status == B.LEET_ERR_UNSUPPORTED
+    qb = torch.zeros(1, 1, 64, 64, device="cuda", dtype=torch.bfloat16)
+    vb = torch.zeros(1, 1, 64, 128, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(B.LeetAttnError) as ei:        # rank 64 with width 128 is not built
+        B.leet_attn_forward_rd(qb, qb, vb, g)
+    assert ei.value.status == B.LEET_ERR_UNSUPPORTED
+    assert B.workspace_bytes_rd(1, 32, 32768, 128, 256, B.LEET_BF16, 8) == 32 * 7 * 128 * 256 * 4
+    assert B.workspace_bytes_rd(1, 32, 32768, 64, 128, B.LEET_BF16, 8) == 0

@@ -373,3 +373,29 @@ def test_prefill_and_decode_replay_from_a_hip_graph(B):
         # eager work of the program between replays
         other = B.leet_attn_forward_ex(dq, dk, dv, dg, segments=2)   # other segment count: equal up to rounding
         assert max_rel_err(other.cpu().numpy(), eager.cpu().numpy()) < TOL["bf16"]
+
+
+# ---------------------------------------------------------------- extremes of the launch geometry
+def test_one_very_long_sequence(B):
+    """One (batch, head) of 262144 tokens: 4096 chunks cut into the maximum number of segments, a long scan."""
+    N, d = 262144, 64
+    say(f"case long sequence N={N} d={d}")
+    nseg, kern = B.query_plan(1, 1, N, d, B.LEET_BF16)
+    assert kern == B.KERNEL_WIDE and nseg > 100
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 1, N, d, "bf16", seed=9, gamma=torch.tensor([0.999]))
+    S = torch.empty(1, 1, d, d, dtype=torch.float32, device="cuda")
+    out = B.leet_attn_forward_ex(*dev(q, k, v, gamma), state_out=S).cpu().numpy()
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out, ref, "bf16", "out")
+    check(S.cpu().numpy(), s_ref, "bf16", "final state")
+
+
+def test_many_short_sequences(B):
+    """2560 (batch, head) pairs of 100 tokens: no segments, one ragged pair of chunks per workgroup."""
+    Bn, H, N, d = 64, 40, 100, 128
+    say(f"case many sequences B={Bn} H={H} N={N}")
+    assert B.query_plan(Bn, H, N, d, B.LEET_BF16) == (1, B.KERNEL_WIDE)
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=10, gamma=W.make_gamma("pow2:1:10", H))
+    out = B.leet_attn_forward(*dev(q, k, v, gamma)).cpu().numpy()
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out, ref, "bf16", "out")

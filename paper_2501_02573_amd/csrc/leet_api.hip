@@ -29,12 +29,13 @@ namespace {
 using leet::kChunk;
 
 // Sequences are cut into segments so that about this many workgroups exist, but no
-// segment is shorter than a minimum number of chunks: each extra segment costs one D x D
+// segment is shorter than a minimum number of chunks: each extra segment costs one D x DV
 // fp32 state written, scanned and re-read, and every segment but the last has its K and V
 // read twice.  The fp32 kernel is bound by MFMA latency per chunk, not by HBM, so it takes
-// much shorter segments than the bf16 kernels.  One workgroup per compute unit of a 256-CU device measured best for both kernel
-// families (the walk is HBM-bound from there on, and fewer segments mean less pre-pass and
-// scan traffic); the column-split bf16 kernel puts D/32 workgroups on a segment.
+// much shorter segments than the 16-bit kernels.  One workgroup per compute unit of a 256-CU
+// device measured best for both kernel families (the walk is HBM-bound from there on, and
+// fewer segments mean less pre-pass and scan traffic; multiples of 256 workgroups beat the
+// counts in between); the column-split bf16 kernel puts D/32 workgroups on a segment.
 constexpr int kTargetWorkgroupsWide = 256;
 constexpr int kTargetWorkgroupsCoop = 256;
 constexpr int kMinSegChunksBf16 = 8;
@@ -47,9 +48,9 @@ std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
 
 // LEET_KERNEL_AUTO: the column-split kernel runs when the column split alone yields about one
 // workgroup per compute unit of a 256-CU device (so no segments, no pre-pass, no scan) and the
-// sequence is long enough to amortise its three-iteration pipeline; there it measured 4 % faster
-// than the wide path (config 3: 92 vs 96.5 us).  With fewer sequences it would need segments and
-// a pre-pass of its own and loses clearly (config 4: 557 vs 378 us); with more, the wide kernel
+// sequence is long enough to amortise its three-iteration pipeline; there it measured 17 % faster
+// than the wide path (config 3: 75 vs 90 us).  With fewer sequences it would need segments and
+// a pre-pass of its own and loses clearly (config 4: 520 vs 348 us); with more, the wide kernel
 // needs few or no segments itself.  A caller that asks for a segment count gets the wide kernel.
 bool auto_picks_column_split(long BH, int D, int nchunks, int segments) {
     const long wgs = BH * (D / 32);

@@ -142,7 +142,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "the path shards over (batch, head) without communication, see DESIGN.md", file=sys.stderr)
+              "the path would shard over (batch, head) without communication", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -198,6 +198,7 @@ int leet_attn_forward_profile(const void *q, const void *k, const void *v, const
  *   mode 1  read: reads `bytes` from src; dst receives one float per workgroup
  *           (dst must hold `workgroups` floats)
  *   mode 2  fill: writes `bytes` to dst (src ignored)
+ *   mode 3  copy, mode 4  fill, with nontemporal stores (how the library writes its outputs)
  *   bytes   multiple of 16; src, dst 16-byte aligned device pointers
  *   workgroups  grid size (256 threads each); each thread strides over the buffer
  * Asynchronous on `stream`.  Not part of the attention path.
@@ -233,6 +234,20 @@ int leet_attn_release_workspace(void);
 typedef enum { LEET_KERNEL_WIDE = 0, LEET_KERNEL_COLUMN_SPLIT = 1, LEET_KERNEL_AUTO = 2 } leet_bf16_kernel;
 int leet_attn_set_bf16_kernel(int which);
 int leet_attn_get_bf16_kernel(void);
+
+/*
+ * Tuning knob: how a decode step stores the updated state.
+ *   LEET_DECODE_STORE_AUTO    (default) streamed when this call's state exceeds half of the 256 MB
+ *                             last-level cache, cached otherwise
+ *   LEET_DECODE_STORE_CACHED  ordinary stores: best when the next step on the same state finds it
+ *                             in the cache (one small model stepping alone)
+ *   LEET_DECODE_STORE_STREAM  nontemporal stores: best when other states are touched before this one
+ *                             is used again (many layers taking turns), whatever its size
+ * The results are identical; only the memory traffic differs.  Process-wide.
+ */
+typedef enum { LEET_DECODE_STORE_AUTO = 0, LEET_DECODE_STORE_CACHED = 1, LEET_DECODE_STORE_STREAM = 2 } leet_decode_store;
+int leet_attn_set_decode_store(int mode);
+int leet_attn_get_decode_store(void);
 
 /*
  * What leet_attn_forward_ex would do for this shape under the current kernel choice (fp32

@@ -38,6 +38,8 @@ EXPORTED_SYMBOLS = (
     "leet_attn_set_bf16_kernel",
     "leet_attn_get_bf16_kernel",
     "leet_attn_query_plan",
+    "leet_attn_set_decode_store",
+    "leet_attn_get_decode_store",
     "leet_attn_workspace_bytes",
     "leet_attn_release_workspace",
     "leet_attn_strerror",
@@ -95,6 +97,10 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_get_bf16_kernel.restype = i
     lib.leet_attn_query_plan.argtypes = [i, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
     lib.leet_attn_query_plan.restype = i
+    lib.leet_attn_set_decode_store.argtypes = [i]
+    lib.leet_attn_set_decode_store.restype = i
+    lib.leet_attn_get_decode_store.argtypes = []
+    lib.leet_attn_get_decode_store.restype = i
     lib.leet_attn_strerror.argtypes = [i]
     lib.leet_attn_strerror.restype = ctypes.c_char_p
     lib.leet_attn_version.argtypes = []
@@ -158,6 +164,19 @@ def set_bf16_kernel(which: int) -> None:
 
 def get_bf16_kernel() -> int:
     return int(lib.leet_attn_get_bf16_kernel())
+
+
+DECODE_STORE_AUTO, DECODE_STORE_CACHED, DECODE_STORE_STREAM = 0, 1, 2
+
+
+def set_decode_store(mode: int) -> None:
+    st = lib.leet_attn_set_decode_store(int(mode))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_set_decode_store")
+
+
+def get_decode_store() -> int:
+    return int(lib.leet_attn_get_decode_store())
 
 
 def query_plan(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0):
@@ -306,7 +325,7 @@ def leet_attn_forward_profile(q, k, v, gamma, out: Optional[torch.Tensor] = None
 def calibration_stream(mode: str, src: Optional[torch.Tensor], dst: torch.Tensor, nbytes: int,
                        workgroups: int = 4096) -> None:
     """Launches the plain copy / read / fill kernel over ``nbytes`` (measurement aid)."""
-    code = {"copy": 0, "read": 1, "fill": 2}[mode]
+    code = {"copy": 0, "read": 1, "fill": 2, "copy_nt": 3, "fill_nt": 4}[mode]
     dev = _check_dev(src, dst)
     with torch.cuda.device(dev):
         st = lib.leet_attn_calibration_stream(code, _ptr(src), _ptr(dst), int(nbytes), int(workgroups),

@@ -54,7 +54,10 @@ hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float*
 // Thread t: columns 4*(t % (DV/4)) .. +3, rows (t / (DV/4)) + RP*m, RP = 1024/DV.
 // ---------------------------------------------------------------------------------
 // kElem: 0 = fp32, 1 = bf16, 2 = fp16 inputs.  gamma == nullptr means gamma = 1.
-template <int D, int DV, int kElem>
+// kStreamStore: the updated state is stored with the nontemporal hint -- right when it will not
+// be read again before it has left the last-level cache (states larger than that cache, or many
+// layers' states taking turns), wrong when the next step finds it there.
+template <int D, int DV, int kElem, bool kStreamStore>
 __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* k, const void* v,
                                                      const float* gamma, float* state, float* out, int H) {
     constexpr int CP = DV / 4;       // threads per state row
@@ -97,7 +100,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* 
             x[e] = fmaf(gm, x[e], kr * vv[e]);
             acc[e] = fmaf(qr, x[e], acc[e]);
         }
-        Sg[(size_t)row * CP + c4] = x;
+        if (kStreamStore) __builtin_nontemporal_store(x, &Sg[(size_t)row * CP + c4]);
+        else Sg[(size_t)row * CP + c4] = x;
     }
 
     // combine the row groups: inside a wave (lanes CP apart), then across the four waves
@@ -114,21 +118,29 @@ __global__ __launch_bounds__(256) void decode_kernel(const void* q, const void* 
     }
 }
 
-template <int D, int DV>
-static void launch_decode_d(const void* q, const void* k, const void* v, const float* gamma, float* state,
+template <int D, int DV, bool kStreamStore>
+static void launch_decode_s(const void* q, const void* k, const void* v, const float* gamma, float* state,
                             float* out, int BH, int H, int elem, hipStream_t stream) {
     dim3 grid(BH), block(256);
-    if (elem == 0) hipLaunchKernelGGL((decode_kernel<D, DV, 0>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    else if (elem == 1) hipLaunchKernelGGL((decode_kernel<D, DV, 1>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
-    else hipLaunchKernelGGL((decode_kernel<D, DV, 2>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    if (elem == 0) hipLaunchKernelGGL((decode_kernel<D, DV, 0, kStreamStore>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else if (elem == 1) hipLaunchKernelGGL((decode_kernel<D, DV, 1, kStreamStore>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+    else hipLaunchKernelGGL((decode_kernel<D, DV, 2, kStreamStore>), grid, block, 0, stream, q, k, v, gamma, state, out, H);
+}
+
+template <int D, int DV>
+static void launch_decode_d(const void* q, const void* k, const void* v, const float* gamma, float* state,
+                            float* out, int BH, int H, int elem, bool stream_store, hipStream_t stream) {
+    if (stream_store) launch_decode_s<D, DV, true>(q, k, v, gamma, state, out, BH, H, elem, stream);
+    else launch_decode_s<D, DV, false>(q, k, v, gamma, state, out, BH, H, elem, stream);
 }
 
 // elem: 0 = fp32, 1 = bf16, 2 = fp16 inputs; (D, DV) one of (64, 64), (128, 128), (128, 256)
 hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
-                         float* out, int BH, int H, int D, int DV, int elem, hipStream_t stream) {
-    if (D == 64) launch_decode_d<64, 64>(q, k, v, gamma, state, out, BH, H, elem, stream);
-    else if (DV == 128) launch_decode_d<128, 128>(q, k, v, gamma, state, out, BH, H, elem, stream);
-    else launch_decode_d<128, 256>(q, k, v, gamma, state, out, BH, H, elem, stream);
+                         float* out, int BH, int H, int D, int DV, int elem, bool stream_store,
+                         hipStream_t stream) {
+    if (D == 64) launch_decode_d<64, 64>(q, k, v, gamma, state, out, BH, H, elem, stream_store, stream);
+    else if (DV == 128) launch_decode_d<128, 128>(q, k, v, gamma, state, out, BH, H, elem, stream_store, stream);
+    else launch_decode_d<128, 256>(q, k, v, gamma, state, out, BH, H, elem, stream_store, stream);
     return hipGetLastError();
 }
 

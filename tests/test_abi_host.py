@@ -125,3 +125,16 @@ def test_binding_rejects_cpu_tensors(lib):
     g = torch.ones(1)
     with pytest.raises(ValueError):
         b.leet_attn_forward(q, q, q, g, torch.empty_like(q))
+
+
+def test_decode_store_knob(lib):
+    from paper_2501_02573_amd import binding as b
+    assert b.get_decode_store() == b.DECODE_STORE_AUTO
+    try:
+        for mode in (b.DECODE_STORE_CACHED, b.DECODE_STORE_STREAM, b.DECODE_STORE_AUTO):
+            b.set_decode_store(mode)
+            assert b.get_decode_store() == mode
+        with pytest.raises(b.LeetAttnError):
+            b.set_decode_store(5)
+    finally:
+        b.set_decode_store(b.DECODE_STORE_AUTO)

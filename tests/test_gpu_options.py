@@ -289,3 +289,25 @@ def test_rank_value_width_combinations_rejected(B):
     assert ei.value.status == B.LEET_ERR_UNSUPPORTED
     assert B.workspace_bytes_rd(1, 32, 32768, 128, 256, B.LEET_BF16, 8) == 32 * 7 * 128 * 256 * 4
     assert B.workspace_bytes_rd(1, 32, 32768, 64, 128, B.LEET_BF16, 8) == 0
+
+
+def test_decode_store_policies_give_identical_results(B):
+    """Cached and streamed state stores differ in memory traffic only."""
+    cfg = W.DecodeConfig("t", 4, 6, 128, 5, 33, "pow2:1:9")
+    results = []
+    try:
+        for mode in (B.DECODE_STORE_CACHED, B.DECODE_STORE_STREAM):
+            B.set_decode_store(mode)
+            state0, gamma, steps = W.decode_stream(cfg)
+            S = state0.cuda(); dg = gamma.cuda()
+            outs = [B.leet_attn_decode_step(*dev(q, k, v), dg, S).clone() for q, k, v in steps]
+            results.append((torch.stack(outs), S.clone()))
+    finally:
+        B.set_decode_store(B.DECODE_STORE_AUTO)
+    assert torch.equal(results[0][0], results[1][0]) and torch.equal(results[0][1], results[1][1])
+    state0, gamma, steps = W.decode_stream(cfg)
+    S_ref = W.to_f64(state0)
+    for n, (q, k, v) in enumerate(steps):
+        o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), W.to_f64(gamma), S_ref)
+        assert max_rel_err(to_np(results[1][0][n]), o_ref) < 1e-5
+    assert max_rel_err(to_np(results[1][1]), S_ref) < 1e-5

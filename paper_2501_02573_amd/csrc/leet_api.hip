@@ -16,7 +16,7 @@ hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStrea
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
-                           int nseg, int seg_tokens, int D, int DV, hipStream_t stream);
+                           int nseg, int seg_tokens, int step, int D, int DV, hipStream_t stream);
 hipError_t launch_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
                             const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
                             int elem, hipStream_t stream);
@@ -64,6 +64,7 @@ std::atomic<int> g_decode_store{LEET_DECODE_STORE_AUTO};
 struct Plan {
     int nseg;
     int seg_chunks;
+    int pre_split;  // the pre-pass and the scan run on segments this many times finer than the walk's
     size_t ws_bytes;
     bool coop;  // the column-split kernel runs this call
 };
@@ -95,7 +96,13 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool plain, int segment
     if (per_seg * (long)nseg >= (1L << 28)) return false;
     plan->nseg = nseg;
     plan->seg_chunks = seg_chunks;
-    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * D * DV * sizeof(float);
+    // The pre-pass is a pure read stream and runs faster with two workgroups per compute unit
+    // (config 4: 6.2 against 4.7 TB/s), the walk does not (more boundary states to carry); so the
+    // 16-bit wide path computes the segment states on half-segments and the walk takes every
+    // second boundary.  Same K and V bytes read, one more state per segment scanned.
+    const bool wide16 = dtype != LEET_F32 && !coop;
+    plan->pre_split = (wide16 && nseg > 1 && seg_chunks >= 16 && seg_chunks % 2 == 0 && per_seg * (nseg - 1) <= 256) ? 2 : 1;
+    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * plan->pre_split * D * DV * sizeof(float);
     return true;
 }
 
@@ -192,10 +199,15 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     p.state_in = state_in; p.state_out = state_out;
     p.seg_state = static_cast<float*>(ws);
     p.H = H; p.N = N; p.nseg = plan.nseg; p.seg_chunks = plan.seg_chunks;
+    p.state_slots = (plan.nseg - 1) * plan.pre_split;
+    p.state_step = plan.pre_split;
     p.no_decay = no_decay ? 1 : 0;
     // Inputs that fit the 256 MB last-level cache are left to it (a pre-pass reads K and V before
     // the walk does, and a caller's next layer may reuse them); larger ones are streamed.
     p.stream_loads = (size_t)BH * N * (2 * d + dv) * (dtype == LEET_F32 ? 4 : 2) > kLastLevelCacheBytes ? 1 : 0;
+    leet::FwdParams pre = p;  // geometry of the pre-pass and of the scan
+    pre.nseg = p.state_slots + 1;
+    pre.seg_chunks = plan.seg_chunks / plan.pre_split;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool in16 = dtype != LEET_F32;
     const bool f16 = dtype == LEET_F16;
@@ -204,11 +216,11 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     const bool coop = plan.coop;
     auto launch_states = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
-               : in16 ? leet::launch_fwd_16bit_states(p, (int)BH, d, dv, f16, s)
+               : in16 ? leet::launch_fwd_16bit_states(pre, (int)BH, d, dv, f16, s)
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
     auto launch_scan = [&]() {
-        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, plan.nseg, plan.seg_chunks * kChunk, d, dv, s);
+        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk, p.state_step, d, dv, s);
     };
     auto launch_walk = [&]() {
         return coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)

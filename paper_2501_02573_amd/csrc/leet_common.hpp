@@ -28,11 +28,13 @@ struct FwdParams {
     void* out;              // [BH][N][D], fp32 or the 16-bit input type
     const float* state_in;  // [BH][D][D] or null: state before token 0
     float* state_out;       // [BH][D][D] or null: state after token N-1
-    float* seg_state;       // [BH][nseg-1][D][D]: slot s-1 holds the state entering segment s
+    float* seg_state;       // [BH][state_slots][D][DV]: slot s*state_step-1 holds the state entering segment s
     int H;
     int N;
     int nseg;        // segments per sequence
     int seg_chunks;  // chunks per segment (all but the last segment)
+    int state_slots; // boundary-state slots per sequence (nseg-1, or more when the pre-pass runs on finer segments)
+    int state_step;  // slots per segment
     int no_decay;    // non-zero: 0/1 causal mask, i.e. gamma = 1 for every head
     int stream_loads;  // non-zero: q, k, v exceed the last-level cache; load them with the nontemporal hint
 };

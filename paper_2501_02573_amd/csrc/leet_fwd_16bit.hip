@@ -161,7 +161,7 @@ __global__ __launch_bounds__(DV * 2, DV > 128 ? 1 : 2) void fwd_16bit_kernel(Fwd
         const float* src = nullptr;
         if (kOut) {
             if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * DV : nullptr;
-            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * DV;
+            else src = p.seg_state + ((size_t)bh * p.state_slots + (seg * p.state_step - 1)) * D * DV;
         }
         if (src) {
 #pragma unroll
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(DV * 2, DV > 128 ? 1 : 2) void fwd_16bit_kernel(Fwd
     if (kOut) {
         if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * DV;
     } else {
-        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * DV;
+        dst = p.seg_state + ((size_t)bh * p.state_slots + seg) * D * DV;
     }
     if (dst) {
 #pragma unroll

@@ -10,12 +10,14 @@ namespace leet {
 // tokens).  On exit slot s holds the true state entering segment s+1:
 //     S_in(0) = state_in or 0 ;  S_in(s+1) = gamma^L S_in(s) + T_s
 // (the block recurrence of Alg. 2 with the decay of Appendix C.1, over segments).
+// Only every `step`-th boundary is written back (slots step-1, 2 step-1, ...): the pre-pass may
+// run on segments `step` times finer than the walk's, which reads no other boundary.
 // One thread per four state elements; the loop over segments is sequential.
 // gamma == nullptr means gamma = 1 for every head (0/1 causal mask).
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const float* state_in,
                                                        const float* gamma, int H, int nseg,
-                                                       int seg_tokens, int DD4, size_t total4) {
+                                                       int seg_tokens, int step, int DD4, size_t total4) {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total4) return;
     int bh = (int)(idx / DD4);
@@ -24,22 +26,31 @@ __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const f
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     if (state_in) acc = reinterpret_cast<const f32x4*>(state_in)[idx];
     f32x4* slot = reinterpret_cast<f32x4*>(seg_state) + (size_t)bh * (nseg - 1) * DD4 + e4;
-    for (int s = 0; s < nseg - 1; ++s) {
-        f32x4 t = slot[(size_t)s * DD4];
-        acc = gl * acc + t;
-        slot[(size_t)s * DD4] = acc;
+    // eight slots at a time: their loads are independent and go out together
+    constexpr int kBatch = 8;
+    for (int s0 = 0; s0 < nseg - 1; s0 += kBatch) {
+        f32x4 t[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (s0 + u < nseg - 1) t[u] = slot[(size_t)(s0 + u) * DD4];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (s0 + u < nseg - 1) {
+                acc = gl * acc + t[u];
+                if ((s0 + u) % step == step - 1) slot[(size_t)(s0 + u) * DD4] = acc;
+            }
     }
 }
 
 // D x DV: shape of one state (rank x value width)
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
-                           int nseg, int seg_tokens, int D, int DV, hipStream_t stream) {
+                           int nseg, int seg_tokens, int step, int D, int DV, hipStream_t stream) {
     if (nseg <= 1) return hipSuccess;
     int DD4 = D * DV / 4;
     size_t total4 = (size_t)BH * DD4;
     unsigned blocks = (unsigned)((total4 + 255) / 256);
     hipLaunchKernelGGL(seg_scan_kernel, dim3(blocks), dim3(256), 0, stream, seg_state, state_in, gamma, H,
-                       nseg, seg_tokens, DD4, total4);
+                       nseg, seg_tokens, step, DD4, total4);
     return hipGetLastError();
 }
 

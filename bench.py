@@ -160,7 +160,7 @@ def main():
     cfg = W.CONFIG3
     nseg3, kern3 = binding.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, binding.LEET_BF16, args.segments)
     kernel_ran = "column-split" if kern3 == binding.KERNEL_COLUMN_SPLIT else "wide"
-    walk_name = {"wide": "fwd_16bit_kernel<128,true,bf16>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[kernel_ran]
+    walk_name = {"wide": "fwd_16bit_kernel<128,128,true,bf16>", "column-split": "fwd_bf16_coop_kernel<128,true>"}[kernel_ran]
     ms_eager, ms_graph, kms, ms_events = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup,
                                                      args.segments, not args.no_graph)
     ms = ms_eager
@@ -257,7 +257,7 @@ def main():
         b5 = c5.B * c5.H * (2 * c5.d * c5.d * 4 + 3 * c5.d * 2 + c5.d * 4)
         extra["decode"] = {
             "workload": c5.name, "us_per_step": ms5 * 1e3, "tokens_per_s": c5.B / (ms5 * 1e-3),
-            "roofline": {"kernel": "decode_kernel<128,bf16>", "bound": "hbm",
+            "roofline": {"kernel": "decode_kernel<128,128,bf16>", "bound": "hbm",
                          "achieved": b5 / (ms5 * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "traffic": load_traffic(c5.name, "decode"),

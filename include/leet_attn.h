@@ -28,8 +28,12 @@
  *     before anything is enqueued: on LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED and
  *     LEET_ERR_TOO_LARGE no buffer has been written.  LEET_ERR_LAUNCH means the HIP
  *     runtime failed part-way; the contents of the output buffers are then undefined.
- *   - d must be 64 or 128.  B, H, N >= 1.  N need not be a multiple of the
- *     chunk length (64 tokens); the last chunk may be ragged.
+ *   - d must be 64 or 128 (the _rd entry points also take rank 128 with value width
+ *     256).  B, H, N >= 1.  N need not be a multiple of the chunk length (64
+ *     tokens); the last chunk may be ragged.
+ *   - Outputs that the library will not read again (prefill `out`) are written
+ *     with nontemporal stores, so that they do not displace the inputs from the
+ *     caches; this changes no value.
  *   - gamma outside [0, 1] is not diagnosed (the values live in device memory).
  */
 #ifndef LEET_ATTN_H
@@ -45,7 +49,7 @@ typedef enum {
     LEET_F32 = 0,  /* q, k, v are IEEE binary32; products on fp32 MFMA              */
     LEET_BF16 = 1, /* q, k, v are bfloat16; products on bf16 MFMA, fp32 accumulate  */
     LEET_F16 = 2   /* q, k, v are IEEE binary16; products on fp16 MFMA, fp32 accumulate
-                      (accepted by the _v2 entry points only)                      */
+                      (accepted by the _v2, _rd and _recurrent entry points)       */
 } leet_dtype;
 
 /*

@@ -139,3 +139,16 @@ def test_decode_store_knob(lib):
             b.set_decode_store(5)
     finally:
         b.set_decode_store(b.DECODE_STORE_AUTO)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as strict C99 and declare every exported symbol."""
+    import subprocess
+    from paper_2501_02573_amd import binding as b
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    calls = "\n".join(f"    (void)&{name};" for name in b.EXPORTED_SYMBOLS)
+    src.write_text('#include "leet_attn.h"\nint main(void) {\n' + calls + "\n    return 0;\n}\n")
+    res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                          "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr

@@ -312,3 +312,15 @@ def test_decode_store_policies_give_identical_results(B):
         o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), W.to_f64(gamma), S_ref)
         assert max_rel_err(to_np(results[1][0][n]), o_ref) < 1e-5
     assert max_rel_err(to_np(results[1][1]), S_ref) < 1e-5
+
+
+def test_usage_example_shape_heads32_rank128_dim256(B):
+    """The shape of the paper's usage example (Section 4): heads 32, rank 128, dim 256; N = 8192, batch 1,
+    in the launch configuration the library picks by itself."""
+    Bn, H, N, r, dv = 1, 32, 8192, 128, 256
+    say(f"case usage-example shape B={Bn} H={H} N={N} r={r} dv={dv}")
+    q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N, r, dv, "bf16", seed=77, gamma=W.make_gamma("pow2:5:10", H))
+    out = B.leet_attn_forward_rd(*dev(q, k, v, gamma))
+    torch.cuda.synchronize()
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(to_np(out), ref, TOL["bf16"], "out (all elements)")

@@ -324,3 +324,43 @@ def test_usage_example_shape_heads32_rank128_dim256(B):
     torch.cuda.synchronize()
     ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
     check(to_np(out), ref, TOL["bf16"], "out (all elements)")
+
+
+# ---------------------------------------------------------------- seeded random legal shapes and options
+def _random_cases(n, seed=2024):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = ["bf16", "f16", "f32"][int(rng.integers(0, 3))]
+        d = int(rng.choice([64, 128]))
+        dv = 256 if (d == 128 and dtype != "f32" and rng.random() < 0.25) else d
+        Bn, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        N = int(rng.choice([1, 17, 64, 65, 127, 128, 300, 511, 900, 1500]))
+        segs = int(rng.choice([0, 0, 1, 2, 3, 7]))
+        out16 = bool(dtype != "f32" and rng.random() < 0.4)
+        causal = bool(rng.random() < 0.25)
+        with_state = bool(rng.random() < 0.5)
+        cases.append((i, Bn, H, N, d, dv, dtype, segs, out16, causal, with_state))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(24), ids=lambda c: "n%d_B%d_H%d_N%d_r%d_dv%d_%s_seg%d_o%d_c%d_s%d" % c)
+def test_random_legal_shapes_and_options(B, case):
+    i, Bn, H, N, d, dv, dtype, segs, out16, causal, with_state = case
+    say(f"case random {case}")
+    rng = np.random.default_rng(100 + i)
+    gamma = torch.from_numpy(rng.uniform(0.0, 1.0, size=H).astype(np.float32))
+    q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N, d, dv, dtype, seed=7000 + i, gamma=gamma)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, dv)) * 0.03).astype(np.float32)) if with_state else None
+    dq, dk, dvv = dev(q, k, v)
+    dg = None if causal else gamma.cuda()
+    ds_in = s_in.cuda() if with_state else None
+    S = torch.empty(Bn, H, d, dv, dtype=torch.float32, device="cuda")
+    odt = W.torch_dtype(dtype) if out16 else torch.float32
+    out = B.leet_attn_forward_rd(dq, dk, dvv, dg, state_in=ds_in, state_out=S, segments=segs, out_dtype=odt,
+                                 mask=B.LEET_MASK_CAUSAL if causal else B.LEET_MASK_DECAY)
+    g_ref = np.ones(H) if causal else W.to_f64(gamma)
+    ref, s_ref = oracle.recurrent(W.to_f64(q), W.to_f64(k), W.to_f64(v), g_ref,
+                                  state_in=None if s_in is None else W.to_f64(s_in))
+    check(to_np(out), ref, TOL[dtype], "out")
+    check(to_np(S), s_ref, TOL[dtype], "final state")

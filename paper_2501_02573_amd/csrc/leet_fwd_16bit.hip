@@ -4,8 +4,9 @@
 // (gamma = 1, the plain causal linear attention of Section 2.2).
 //
 // One workgroup walks the 64-token chunks of one segment of one (batch, head)
-// sequence in order (the loop of Alg. 2, Appendix B.2), carrying the d x d state S
-// in MFMA accumulators.  With the decaying mask (Section 2.2, Eq. "BCMV"), chunk t of
+// sequence in order (the loop of Alg. 2, Appendix B.2), carrying the D x DV state S
+// in MFMA accumulators (D = width of the q and k rows, the paper's rank r; DV = width of
+// the v and out rows; DV = D except for rank 128 with width 256).  With the decaying mask (Section 2.2, Eq. "BCMV"), chunk t of
 // length L computes, using the row/column weight split of Alg. 4 (Appendix B.3):
 //
 //     O_t     = ((Q_t K_t^T) .* D) V_t + Lam (Q_t S_t)       D[i][j] = gamma^(i-j), i >= j
@@ -41,6 +42,11 @@
 // A ragged last chunk (L < 64) is right-aligned in the tile: rows 64-L.. hold the
 // tokens, rows above are zero.  The intra-chunk weights depend on i-j only and Gam on
 // 63-j', so both stay valid; only Lam and gamma^L are taken from the table.
+//
+// Memory policy: chunk tiles are fetched one chunk ahead into registers (16-byte loads; with
+// the nontemporal hint when the inputs exceed the last-level cache); O leaves through a
+// wave-private LDS tile in whole row pieces with nontemporal stores, since nothing here reads
+// it again and written normally it displaces the inputs from the caches.
 #include "leet_common.hpp"
 
 namespace leet {

@@ -16,10 +16,12 @@ once into a HIP graph and replayed (reported for comparison, it measured no fast
 with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle (recurrent form)
 timed on this host's cores on the same workload.
 
-Defaults: 1000 warm-up steps and 1000 timed steps (about 150 ms of GPU work for the headline
-leg).  The device's clocks take on the order of 100 ms of continuous work to settle (kernel
-durations in a profiler trace fall steadily over the first several hundred launches), so much
-shorter runs read 10-25 % slower.
+The device's clocks take on the order of 100 ms of continuous work to settle (kernel durations in
+a profiler trace fall steadily over the first several hundred launches), so short runs from an
+idle device read 10-25 % slower.  Two things keep that out of the figures: before each timed
+section the device is kept busy for --settle-ms (default 250 ms) with a plain copy kernel on
+buffers of its own -- conditioning, not workload, and outside every timed region -- and the
+defaults are long (1000 warm-up and 1000 timed steps).
 """
 from __future__ import annotations
 
@@ -42,6 +44,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=1000)
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="keep the device busy this long with a plain copy kernel before each timed section, "
+                         "so that its clocks have settled whatever --warmup is (0 disables)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
     ap.add_argument("--no-graph", action="store_true", help="time plain calls only (no HIP graph replay)")
@@ -63,8 +68,24 @@ def alg_flops_forward(cfg):
     return cfg.B * cfg.H * cfg.N * (4 * cfg.d * cfg.d + 2 * 64 * cfg.d)
 
 
+_SETTLE = {"ms": 0.0, "fn": None}
+
+
+def settle(torch):
+    """Device conditioning, outside every timed region and not part of the workload: a plain copy
+    kernel (64 MiB buffers, not the workload's) keeps the GPU busy until its clocks have settled."""
+    if _SETTLE["ms"] <= 0 or _SETTLE["fn"] is None:
+        return
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < _SETTLE["ms"]:
+        for _ in range(50):
+            _SETTLE["fn"]()
+        torch.cuda.synchronize()
+
+
 def time_eager(torch, step, steps, warmup):
     """(host-clock ms per step, HIP-event ms per step) over exactly `steps` plain calls."""
+    settle(torch)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -91,6 +112,7 @@ def time_graph(torch, step, steps, warmup):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
+        settle(torch)
         for _ in range(warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -156,6 +178,12 @@ def main():
     binding.set_bf16_kernel({"auto": binding.KERNEL_AUTO, "wide": binding.KERNEL_WIDE,
                              "column-split": binding.KERNEL_COLUMN_SPLIT}[args.kernel])
 
+    _SETTLE["ms"] = args.settle_ms
+    if args.settle_ms > 0:
+        sa = torch.zeros(16 << 20, dtype=torch.float32, device=dev)
+        sb = torch.empty_like(sa)
+        _SETTLE["fn"] = lambda: binding.calibration_stream("copy", sa, sb, sa.numel() * 4, 4096)
+
     # ---------------- headline: config 3
     cfg = W.CONFIG3
     nseg3, kern3 = binding.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, binding.LEET_BF16, args.segments)
@@ -180,6 +208,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_ms": args.settle_ms,
         "ms_per_step": ms,
         "higher_is_better": True,
         "scaling": "weak",
@@ -243,6 +272,7 @@ def main():
         gamma5 = gamma5.to(dev)
         qkv = [tuple(t.to(dev) for t in next(steps_it)) for _ in range(4)]
         o = torch.empty((c5.B, c5.H, c5.d), dtype=torch.float32, device=dev)
+        settle(torch)
         for i in range(16):
             binding.leet_attn_decode_step(*qkv[i % 4], gamma5, S, o)
         e0 = torch.cuda.Event(enable_timing=True)

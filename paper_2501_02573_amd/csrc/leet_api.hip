@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation, segment planning, workspace, launches.
 // Every step of the computation runs in the HIP kernels; nothing here touches tensor data.
 #include <atomic>
+#include <math.h>
 #include <mutex>
 #include <stdlib.h>
 #include <string.h>
@@ -29,34 +30,19 @@ namespace {
 
 using leet::kChunk;
 
-// Sequences are cut into segments so that about this many workgroups exist, but no
-// segment is shorter than a minimum number of chunks: each extra segment costs one D x DV
-// fp32 state written, scanned and re-read, and every segment but the last has its K and V
-// read twice.  The fp32 kernel is bound by MFMA latency per chunk, not by HBM, so it takes
-// much shorter segments than the 16-bit kernels.  One workgroup per compute unit of a 256-CU
-// device measured best for both kernel families (the walk is HBM-bound from there on, and
-// fewer segments mean less pre-pass and scan traffic; multiples of 256 workgroups beat the
-// counts in between); the column-split bf16 kernel puts D/32 workgroups on a segment.
-constexpr int kTargetWorkgroupsWide = 256;
-constexpr int kTargetWorkgroupsCoop = 256;
-constexpr int kMinSegChunksBf16 = 8;
+// fp32 and the rank-128, width-256 shape: sequences are cut into segments so that about this many
+// workgroups exist (one per compute unit of a 256-CU device measured best), but no segment is
+// shorter than a minimum number of chunks: each extra segment costs one D x DV fp32 state written,
+// scanned and re-read, and every segment but the last has its K and V read twice.  The fp32
+// kernel is bound by MFMA latency per chunk, not by HBM, so it takes much shorter segments.
+constexpr int kTargetWorkgroups = 256;
+constexpr int kMinSegChunks16 = 8;
 constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;  // MI355X Infinity Cache
 
 // Kernel choice for bf16 prefill: a leet_bf16_kernel value; LEET_KERNEL_AUTO unless the caller sets one.
 std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
-
-// LEET_KERNEL_AUTO: the column-split kernel runs when the column split alone yields about one
-// workgroup per compute unit of a 256-CU device (so no segments, no pre-pass, no scan) and the
-// sequence is long enough to amortise its three-iteration pipeline; there it measured 17 % faster
-// than the wide path (config 3: 75 vs 90 us).  With fewer sequences it would need segments and
-// a pre-pass of its own and loses clearly (config 4: 520 vs 348 us); with more, the wide kernel
-// needs few or no segments itself.  A caller that asks for a segment count gets the wide kernel.
-bool auto_picks_column_split(long BH, int D, int nchunks, int segments) {
-    const long wgs = BH * (D / 32);
-    return segments == 0 && wgs >= 224 && wgs <= 288 && nchunks >= 16;
-}
 
 // Decode-state store policy: a leet_decode_store value.
 std::atomic<int> g_decode_store{LEET_DECODE_STORE_AUTO};
@@ -69,41 +55,138 @@ struct Plan {
     bool coop;  // the column-split kernel runs this call
 };
 
+// The pre-pass is a pure read stream and runs faster with two workgroups per compute unit
+// (config 4: 6.2 against 4.7 TB/s), the walk does not (more boundary states to carry); so the
+// 16-bit wide path computes the segment states on half-segments and the walk takes every
+// second boundary.  Same K and V bytes read, one more state per segment scanned.
+int wide_pre_split(long BH, int nseg, int seg_chunks) {
+    return (nseg > 1 && seg_chunks >= 16 && seg_chunks % 2 == 0 && BH * (nseg - 1) <= 256) ? 2 : 1;
+}
+
+// Cost model of the 16-bit square shapes (d = 64, 128), in microseconds, for one (kernel, segment
+// count) pair.  Each kernel is priced as the smooth maximum (x^p + y^p)^(1/p) of its dependent
+// chain (rounds of resident workgroups x chunks per segment x the per-chunk time of a lone
+// workgroup) and of its HBM/last-level-cache transfer time; a call is the sum of its kernels plus
+// a fixed cost per call.  The constants are a least-squares fit (6 % rms) to event-timed runs of
+// both kernels at 1 to 64 segments over B*H in 1..256 and N in 256..65536; the tabulated runs are
+// kept with the profiles, and a host test checks the planner's picks against them.
+struct CostModel {
+    double wide_chunk_us, wide_pre_chunk_us;    // lone wide workgroup: walk and pre-pass per chunk
+    double coop_chunk_us, coop_pre_chunk_us;    // column-split workgroups of one sequence, likewise
+    double wide_bw_cached, wide_bw_streamed;    // bytes per us: inputs within / beyond the last-level cache
+    double coop_bw_cached, coop_bw_streamed;
+    double one_kernel_us, three_kernel_us;      // fixed cost of a call without / with pre-pass and scan
+    double scan_state_us;                       // scan latency per segment state
+    double wide_p, coop_p;                      // smooth-maximum exponents
+    double wide_crowded;                        // transfer-time factor with more wide workgroups than CUs
+    int wide_slots;                             // wide workgroups resident on the device
+};
+constexpr CostModel kCost128 = {2.589, 0.847, 0.908, 0.410, 8.0e6, 6.497e6, 6.056e6, 4.554e6,
+                                4.91, 11.32, 0.351, 2.204, 2.0, 1.243, 512};
+constexpr CostModel kCost64 = {1.847, 0.509, 0.645, 0.357, 7.487e6, 6.026e6, 8.0e6, 4.833e6,
+                               4.21, 10.37, 0.347, 2.632, 2.139, 1.135, 1024};
+constexpr double kOneKernelFloorUs = 11.0;    // shortest call seen end to end, one and three kernels
+constexpr double kThreeKernelFloorUs = 17.0;
+constexpr int kCoopSlots = 256;               // one column-split workgroup per compute unit
+
+double smooth_max(double a, double b, double p) { return pow(pow(a, p) + pow(b, p), 1.0 / p); }
+
+// nseg is a segment count that make_plan has already rounded (nseg = ceil(nchunks / seg_chunks))
+double predicted_us(bool coop, long BH, int N, int D, int nseg, int seg_chunks) {
+    const CostModel& m = D == 128 ? kCost128 : kCost64;
+    const double in_bytes = (double)BH * N * D * 6, out_bytes = (double)BH * N * D * 4;
+    // share of the inputs that no longer stays in the last-level cache: none up to 0.6 of its size
+    // (the outputs pass through it too), all from 1.2
+    const double spill = fmin(1.0, fmax(0.0, (in_bytes / (double)kLastLevelCacheBytes - 0.6) / 0.6));
+    const double pre_bytes = (double)BH * N * D * 4 * (nseg - 1) / nseg;  // K and V of all segments but the last
+    double scan = nseg > 1 ? nseg * fmax(m.scan_state_us, (double)BH * D * D * 8 / 5e6) : 0.0;
+    if (coop) {
+        const long per_seg = BH * (D / 32);
+        const double bw = m.coop_bw_cached * (1.0 - spill) + m.coop_bw_streamed * spill;
+        const long rounds = (per_seg * nseg + kCoopSlots - 1) / kCoopSlots;
+        const double walk = smooth_max(rounds * seg_chunks * m.coop_chunk_us, (in_bytes + out_bytes) / bw, m.coop_p);
+        if (nseg == 1) return fmax(kOneKernelFloorUs, m.one_kernel_us + walk);
+        const long pre_rounds = (per_seg * (nseg - 1) + kCoopSlots - 1) / kCoopSlots;
+        const double pre = smooth_max(pre_rounds * seg_chunks * m.coop_pre_chunk_us, pre_bytes / bw, m.coop_p);
+        return fmax(kThreeKernelFloorUs, m.three_kernel_us + walk + pre + scan);
+    }
+    const double bw = m.wide_bw_cached * (1.0 - spill) + m.wide_bw_streamed * spill;
+    const long W = BH * nseg;
+    const long rounds = (W + m.wide_slots - 1) / m.wide_slots;
+    const double walk = smooth_max(rounds * seg_chunks * m.wide_chunk_us,
+                                   (in_bytes + out_bytes) / bw * (W > 256 ? m.wide_crowded : 1.0), m.wide_p);
+    if (nseg == 1) return fmax(kOneKernelFloorUs, m.one_kernel_us + walk);
+    const int split = wide_pre_split(BH, nseg, seg_chunks);
+    const long pre_rounds = (BH * (nseg - 1) * split + m.wide_slots - 1) / m.wide_slots;
+    const double pre = smooth_max(pre_rounds * (seg_chunks / split) * m.wide_pre_chunk_us, pre_bytes / bw, m.wide_p);
+    return fmax(kThreeKernelFloorUs, m.three_kernel_us + walk + pre + scan * split);
+}
+
 // plain = fp32 output and decaying mask, the only form the column-split kernel implements
 // D: width of q and k rows (rank); DV: width of v and out rows
+//
+// 16-bit square shapes: every eligible (kernel, segment count) pair is priced with the cost model
+// and the cheapest taken (ties go to fewer segments, then to the column-split kernel).  A caller's
+// segment count or kernel choice narrows the candidates.  Other shapes and fp32 keep the rule of
+// about one workgroup per compute unit with a minimum segment length.
 bool make_plan(long BH, int N, int D, int DV, int dtype, bool plain, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
     const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
-    const bool coop = dtype == LEET_BF16 && plain && D == DV &&
-                      (choice == LEET_KERNEL_COLUMN_SPLIT ||
-                       (choice == LEET_KERNEL_AUTO && auto_picks_column_split(BH, D, nchunks, segments)));
-    plan->coop = coop;
-    const long per_seg = coop ? BH * (D / 32) : BH;   // workgroups one segment of every sequence gives
-    const long target = coop ? kTargetWorkgroupsCoop : kTargetWorkgroupsWide;
+    const bool coop_able = dtype == LEET_BF16 && plain && D == DV;
+    auto finish = [&](bool coop, int nseg, int seg_chunks) {
+        const long per_seg = coop ? BH * (D / 32) : BH;  // workgroups one segment of every sequence gives
+        if (per_seg * (long)nseg >= (1L << 28)) return false;
+        plan->coop = coop;
+        plan->nseg = nseg;
+        plan->seg_chunks = seg_chunks;
+        plan->pre_split = (dtype != LEET_F32 && !coop) ? wide_pre_split(BH, nseg, seg_chunks) : 1;
+        plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * plan->pre_split * D * DV * sizeof(float);
+        return true;
+    };
+    auto round_segments = [&](long want, int* nseg, int* seg_chunks) {
+        if (want < 1) want = 1;
+        if (want > nchunks) want = nchunks;
+        *seg_chunks = (int)((nchunks + want - 1) / want);
+        *nseg = (nchunks + *seg_chunks - 1) / *seg_chunks;
+    };
+
+    if (dtype != LEET_F32 && D == DV) {
+        // the column-split kernel needs four chunks to fill its pipeline and is not offered below
+        const bool try_coop = coop_able && choice != LEET_KERNEL_WIDE && (nchunks >= 4 || choice == LEET_KERNEL_COLUMN_SPLIT);
+        const bool try_wide = !(coop_able && choice == LEET_KERNEL_COLUMN_SPLIT);
+        static const int kCounts[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
+        double best = 0.0;
+        bool have = false, best_coop = false;
+        int best_nseg = 1, best_chunks = nchunks;
+        for (int want : kCounts) {
+            if (segments > 0) want = segments;
+            int nseg, seg_chunks;
+            round_segments(want, &nseg, &seg_chunks);
+            if (segments == 0 && nseg > 1 && seg_chunks < 2) break;
+            for (int c = 1; c >= 0; --c) {
+                if (c ? !try_coop : !try_wide) continue;
+                const double t = predicted_us(c != 0, BH, N, D, nseg, seg_chunks);
+                if (!have || t < best * 0.98) {
+                    have = true; best = t; best_coop = c != 0; best_nseg = nseg; best_chunks = seg_chunks;
+                }
+            }
+            if (segments > 0) break;
+        }
+        return finish(best_coop, best_nseg, best_chunks);
+    }
+
     long want;
     if (segments > 0) {
         want = segments;
     } else {
-        want = (target + per_seg - 1) / per_seg;
-        long cap = nchunks / (dtype == LEET_F32 ? kMinSegChunksF32 : kMinSegChunksBf16);
+        want = (kTargetWorkgroups + BH - 1) / BH;
+        long cap = nchunks / (dtype == LEET_F32 ? kMinSegChunksF32 : kMinSegChunks16);
         if (cap < 1) cap = 1;
         if (want > cap) want = cap;
     }
-    if (want < 1) want = 1;
-    if (want > nchunks) want = nchunks;
-    const int seg_chunks = (int)((nchunks + want - 1) / want);
-    const int nseg = (nchunks + seg_chunks - 1) / seg_chunks;
-    if (per_seg * (long)nseg >= (1L << 28)) return false;
-    plan->nseg = nseg;
-    plan->seg_chunks = seg_chunks;
-    // The pre-pass is a pure read stream and runs faster with two workgroups per compute unit
-    // (config 4: 6.2 against 4.7 TB/s), the walk does not (more boundary states to carry); so the
-    // 16-bit wide path computes the segment states on half-segments and the walk takes every
-    // second boundary.  Same K and V bytes read, one more state per segment scanned.
-    const bool wide16 = dtype != LEET_F32 && !coop;
-    plan->pre_split = (wide16 && nseg > 1 && seg_chunks >= 16 && seg_chunks % 2 == 0 && per_seg * (nseg - 1) <= 256) ? 2 : 1;
-    plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * plan->pre_split * D * DV * sizeof(float);
-    return true;
+    int nseg, seg_chunks;
+    round_segments(want, &nseg, &seg_chunks);
+    return finish(false, nseg, seg_chunks);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -94,18 +94,32 @@ def test_kernel_choice_setter_and_plan_query(lib):
     from paper_2501_02573_amd import binding as b
     assert b.get_bf16_kernel() == b.KERNEL_AUTO
     try:
-        # automatic choice: column split where it alone gives about one workgroup per compute unit
-        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # 256 workgroups
-        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16, 4) == (4, b.KERNEL_WIDE)          # caller asked for segments
-        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16) == (8, b.KERNEL_WIDE)            # too few sequences
+        # automatic choice: the cheapest (kernel, segment count) pair by the library's cost model
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # 256 workgroups, one kernel
+        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16)[1] == b.KERNEL_WIDE              # inputs beyond the cache
         assert b.query_plan(16, 32, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_WIDE)            # plenty of sequences
-        assert b.query_plan(4, 16, 512, 128, b.LEET_BF16)[1] == b.KERNEL_WIDE                # too short
+        assert b.query_plan(4, 16, 128, 128, b.LEET_BF16) == (1, b.KERNEL_WIDE)              # two chunks: too short
+        assert b.query_plan(4, 16, 512, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)
+        assert b.query_plan(2, 16, 1024, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # small job: launches dominate
+        assert b.query_plan(2, 16, 4096, 128, b.LEET_BF16) == (8, b.KERNEL_WIDE)             # half the device, long
+        assert b.query_plan(4, 18, 4096, 128, b.LEET_BF16)[1] == b.KERNEL_WIDE               # 288 workgroups: a second round
+        assert b.query_plan(4, 15, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # 240 workgroups, whole sequences
+        assert b.query_plan(4, 16, 16384, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)            # inputs beyond the cache
+        assert b.query_plan(8, 16, 16384, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # d = 64: two slices a sequence
+        assert b.query_plan(8, 16, 4096, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)
         assert b.query_plan(4, 16, 4096, 128, b.LEET_F32)[1] == b.KERNEL_WIDE                # bf16 only
-        assert b.query_plan(8, 16, 4096, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # d = 64: two slices
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_F16)[1] == b.KERNEL_WIDE
+        # a lone sequence: many short segments of the column-split kernel
+        nseg, kern = b.query_plan(1, 1, 4096, 128, b.LEET_BF16)
+        assert kern == b.KERNEL_COLUMN_SPLIT and 8 <= nseg <= 16
+        # a caller's segment count is kept; the kernel is still chosen
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16, 4) == (4, b.KERNEL_WIDE)
+        assert b.query_plan(1, 1, 4096, 128, b.LEET_BF16, 8) == (8, b.KERNEL_COLUMN_SPLIT)
         assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 0
         b.set_bf16_kernel(b.KERNEL_COLUMN_SPLIT)
         assert b.get_bf16_kernel() == b.KERNEL_COLUMN_SPLIT
-        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16) == (2, b.KERNEL_COLUMN_SPLIT)
+        assert b.query_plan(1, 32, 32768, 128, b.LEET_BF16)[1] == b.KERNEL_COLUMN_SPLIT
+        assert b.query_plan(4, 16, 128, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)      # forced: any length
         b.set_bf16_kernel(b.KERNEL_WIDE)
         assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)
         # four segments for the walk, boundary states on half-segments for the pre-pass and the scan
@@ -117,6 +131,28 @@ def test_kernel_choice_setter_and_plan_query(lib):
             b.query_plan(1, 1, 64, 96, b.LEET_BF16)
     finally:
         b.set_bf16_kernel(b.KERNEL_AUTO)
+
+
+def test_planner_against_measured_sweep(lib):
+    """The planner's pick is within 12 % of the fastest measured (kernel, segment count) pair on every
+    shape of the tabulated sweep, and within 1 % on average."""
+    import json
+    from paper_2501_02573_amd import binding as b
+    table = json.load(open(os.path.join(ROOT, "profiles", "plan_sweep.json")))
+    ratios = []
+    for key, runs in table.items():
+        if key.startswith("_"):
+            continue
+        d, bh, n = (int(x) for x in key.split(","))
+        nseg, kern = b.query_plan(1, bh, n, d, b.LEET_BF16)
+        label = ("c" if kern == b.KERNEL_COLUMN_SPLIT else "w") + str(nseg)
+        if label not in runs:      # a rounded segment count that the sweep did not time
+            continue
+        ratio = runs[label] / min(runs.values())
+        assert ratio <= 1.12, (key, label, runs[label], min(runs.values()))
+        ratios.append(ratio)
+    assert len(ratios) >= 150
+    assert sum(ratios) / len(ratios) <= 1.01
 
 
 def test_binding_rejects_cpu_tensors(lib):

@@ -91,8 +91,12 @@ def test_fp16_inputs_and_16bit_outputs(B, shape):
     check(to_np(s_out), s_ref2, TOL[dtype], "with state_in: final state")
 
     if out16:
-        # the 16-bit output is the fp32 output of the same kernel, rounded to nearest even
-        out32 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=segs)
+        # the 16-bit output is the fp32 output of the same (wide) kernel, rounded to nearest even
+        B.set_bf16_kernel(B.KERNEL_WIDE)
+        try:
+            out32 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=segs)
+        finally:
+            B.set_bf16_kernel(B.KERNEL_AUTO)
         assert torch.equal(out32.to(odt), out2), "16-bit output is not the rounded fp32 output"
 
 

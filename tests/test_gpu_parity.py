@@ -377,15 +377,39 @@ def test_prefill_and_decode_replay_from_a_hip_graph(B):
 
 # ---------------------------------------------------------------- extremes of the launch geometry
 def test_one_very_long_sequence(B):
-    """One (batch, head) of 262144 tokens: 4096 chunks cut into the maximum number of segments, a long scan."""
+    """One (batch, head) of 262144 tokens: 4096 chunks cut into many segments, a long scan."""
     N, d = 262144, 64
     say(f"case long sequence N={N} d={d}")
     nseg, kern = B.query_plan(1, 1, N, d, B.LEET_BF16)
-    assert kern == B.KERNEL_WIDE and nseg > 100
+    assert nseg >= 32
     q, k, v, gamma = W.make_custom_forward_inputs(1, 1, N, d, "bf16", seed=9, gamma=torch.tensor([0.999]))
     S = torch.empty(1, 1, d, d, dtype=torch.float32, device="cuda")
     out = B.leet_attn_forward_ex(*dev(q, k, v, gamma), state_out=S).cpu().numpy()
     ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out, ref, "bf16", "out")
+    check(S.cpu().numpy(), s_ref, "bf16", "final state")
+
+
+PLANNED_SHAPES = [
+    (1, 1, 3000, 128), (1, 2, 1000, 128), (1, 3, 8192, 64), (2, 2, 5000, 128), (1, 5, 2100, 64),
+    (1, 8, 1536, 128), (1, 12, 3072, 128), (1, 1, 300, 128), (1, 24, 3072, 64),
+]
+
+
+@pytest.mark.parametrize("shape", PLANNED_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d" % s)
+def test_few_sequences_with_the_plans_the_library_picks(B, shape):
+    """Few (batch, head) pairs: the planner cuts them into many short segments, mostly of the
+    column-split kernel.  State in and out, ragged lengths, the library's own plan."""
+    Bn, H, N, d = shape
+    plan = B.query_plan(Bn, H, N, d, B.LEET_BF16)
+    say(f"case few sequences shape={shape} plan (segments, kernel)={plan}")
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=700 + N, gamma=W.make_gamma("pow2:3:10", H) if H > 1 else torch.tensor([0.998]))
+    rng = np.random.default_rng(N + 7)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.02).astype(np.float32))
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    S = torch.empty_like(ds_in)
+    out = B.leet_attn_forward_ex(dq, dk, dv, dg, state_in=ds_in, state_out=S).cpu().numpy()
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
     check(out, ref, "bf16", "out")
     check(S.cpu().numpy(), s_ref, "bf16", "final state")
 

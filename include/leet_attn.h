@@ -229,9 +229,11 @@ int leet_attn_release_workspace(void);
  *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns
  *   LEET_KERNEL_COLUMN_SPLIT  d/32 workgroups per (sequence, segment), 32 value columns each,
  *                             placed on one XCD; fewer segments needed to fill the device
- *                             (bf16 in, fp32 out, decaying mask only; other forms run wide)
- *   LEET_KERNEL_AUTO          (default) column-split where it measured faster -- B*H*d/32 close
- *                             to the number of compute units, N >= 1024, segments = 0 -- else wide
+ *                             (bf16 in, fp32 out only; other forms run wide)
+ *   LEET_KERNEL_AUTO          (default) the library prices both kernels at each candidate segment
+ *                             count with a cost model fitted to measurements and takes the
+ *                             cheapest pair; leet_attn_query_plan reports the outcome
+ * With WIDE or COLUMN_SPLIT set, only the segment count is chosen that way.
  * Process-wide; takes effect for calls made after it returns.  Returns LEET_ERR_INVALID_ARG for
  * any other value.
  */

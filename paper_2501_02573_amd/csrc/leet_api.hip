@@ -122,7 +122,7 @@ double predicted_us(bool coop, long BH, int N, int D, int nseg, int seg_chunks) 
     return fmax(kThreeKernelFloorUs, m.three_kernel_us + walk + pre + scan * split);
 }
 
-// plain = fp32 output and decaying mask, the only form the column-split kernel implements
+// plain = fp32 output, the only form the column-split kernel implements (either mask)
 // D: width of q and k rows (rank); DV: width of v and out rows
 //
 // 16-bit square shapes: every eligible (kernel, segment count) pair is priced with the cost model
@@ -261,7 +261,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dv, dtype, out_dtype == LEET_F32 && !no_decay, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dv, dtype, out_dtype == LEET_F32, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;

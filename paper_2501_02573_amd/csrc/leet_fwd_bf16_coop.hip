@@ -166,7 +166,7 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     float* og = static_cast<float*>(p.out) + seq_off;
 
     {
-        const double gd = (double)p.gamma[h];
+        const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
         for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);
     }
 

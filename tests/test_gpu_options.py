@@ -132,6 +132,29 @@ def test_causal_mask_is_gamma_one(B, shape):
     assert max_rel_err(to_np(out_c), to_np(out)) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("shape", [(1, 3, 777, 64, 2), (2, 4, 2048, 128, 0), (1, 1, 4000, 128, 0), (1, 2, 333, 128, 1)],
+                         ids=lambda s: "B%d_H%d_N%d_d%d_seg%d" % s)
+def test_causal_mask_on_the_column_split_kernel(B, shape):
+    """The 0/1 mask through the column-split bf16 kernel (forced), with an entering state."""
+    Bn, H, N, d, segs = shape
+    say(f"case shape={shape}")
+    q, k, v, _ = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=3100 + N + d)
+    ones = torch.ones(H, dtype=torch.float32)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.1).astype(np.float32))
+    dq, dk, dv, ds_in = dev(q, k, v, s_in)
+    s_out = torch.empty_like(ds_in)
+    B.set_bf16_kernel(B.KERNEL_COLUMN_SPLIT)
+    try:
+        assert B.query_plan(Bn, H, N, d, B.LEET_BF16, segs)[1] == B.KERNEL_COLUMN_SPLIT
+        out = B.leet_attn_forward_v2(dq, dk, dv, None, state_in=ds_in, state_out=s_out, segments=segs, mask=B.LEET_MASK_CAUSAL)
+    finally:
+        B.set_bf16_kernel(B.KERNEL_AUTO)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, ones)), state_in=W.to_f64(s_in))
+    check(to_np(out), ref, TOL["bf16"], "causal mask, column split: out")
+    check(to_np(s_out), s_ref, TOL["bf16"], "causal mask, column split: final state")
+
+
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("f16", 64), ("bf16", 128)])
 def test_decode_v2_dtypes_and_causal_mask(B, dtype, d):
     say(f"case decode_v2 dtype={dtype} d={d}")

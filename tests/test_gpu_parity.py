@@ -274,7 +274,7 @@ def test_wide_kernel_headline_config(wide_only):
 
 
 def test_automatic_kernel_choice_with_state_hand_off(B):
-    """A shape in the band where the column-split kernel is chosen: ragged length, state in and out,
+    """A shape for which the planner picks the column-split kernel on whole sequences: ragged length, state in and out,
     continued by a decode step; compared with the oracle and with the wide path."""
     Bn, H, N, d = 4, 16, 1100, 128
     assert B.get_bf16_kernel() == B.KERNEL_AUTO

@@ -224,12 +224,12 @@ size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segm
 int leet_attn_release_workspace(void);
 
 /*
- * Tuning knob: which kernel a bf16 prefill uses.  Both compute the same chunked form (Alg. 2
+ * Tuning knob: which kernel a bf16 or fp16 prefill uses.  Both compute the same chunked form (Alg. 2
  * with the decaying mask) and pass the same parity tests; they differ in how the work is split.
  *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns
  *   LEET_KERNEL_COLUMN_SPLIT  d/32 workgroups per (sequence, segment), 32 value columns each,
  *                             placed on one XCD; fewer segments needed to fill the device
- *                             (bf16 in, fp32 out only; other forms run wide)
+ *                             (16-bit inputs, square shapes; other forms run wide)
  *   LEET_KERNEL_AUTO          (default) the library prices both kernels at each candidate segment
  *                             count with a cost model fitted to measurements and takes the
  *                             cheapest pair; leet_attn_query_plan reports the outcome

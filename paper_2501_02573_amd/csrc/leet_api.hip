@@ -12,8 +12,8 @@
 namespace leet {
 hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
 hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
-hipError_t launch_fwd_bf16_coop_states(const FwdParams& p, int BH, int D, hipStream_t stream);
-hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
+hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream);
+hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
@@ -92,9 +92,9 @@ constexpr int kCoopSlots = 256;               // one column-split workgroup per 
 double smooth_max(double a, double b, double p) { return pow(pow(a, p) + pow(b, p), 1.0 / p); }
 
 // nseg is a segment count that make_plan has already rounded (nseg = ceil(nchunks / seg_chunks))
-double predicted_us(bool coop, long BH, int N, int D, int nseg, int seg_chunks) {
+double predicted_us(bool coop, long BH, int N, int D, bool out16, int nseg, int seg_chunks) {
     const CostModel& m = D == 128 ? kCost128 : kCost64;
-    const double in_bytes = (double)BH * N * D * 6, out_bytes = (double)BH * N * D * 4;
+    const double in_bytes = (double)BH * N * D * 6, out_bytes = (double)BH * N * D * (out16 ? 2 : 4);
     // share of the inputs that no longer stays in the last-level cache: none up to 0.6 of its size
     // (the outputs pass through it too), all from 1.2
     const double spill = fmin(1.0, fmax(0.0, (in_bytes / (double)kLastLevelCacheBytes - 0.6) / 0.6));
@@ -122,17 +122,17 @@ double predicted_us(bool coop, long BH, int N, int D, int nseg, int seg_chunks) 
     return fmax(kThreeKernelFloorUs, m.three_kernel_us + walk + pre + scan * split);
 }
 
-// plain = fp32 output, the only form the column-split kernel implements (either mask)
+// out16: the output is written in the (16-bit) input type
 // D: width of q and k rows (rank); DV: width of v and out rows
 //
 // 16-bit square shapes: every eligible (kernel, segment count) pair is priced with the cost model
 // and the cheapest taken (ties go to fewer segments, then to the column-split kernel).  A caller's
 // segment count or kernel choice narrows the candidates.  Other shapes and fp32 keep the rule of
 // about one workgroup per compute unit with a minimum segment length.
-bool make_plan(long BH, int N, int D, int DV, int dtype, bool plain, int segments, Plan* plan) {
+bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
     const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
-    const bool coop_able = dtype == LEET_BF16 && plain && D == DV;
+    const bool coop_able = dtype != LEET_F32 && D == DV;  // the column-split kernel: 16-bit inputs, square shapes
     auto finish = [&](bool coop, int nseg, int seg_chunks) {
         const long per_seg = coop ? BH * (D / 32) : BH;  // workgroups one segment of every sequence gives
         if (per_seg * (long)nseg >= (1L << 28)) return false;
@@ -165,7 +165,7 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool plain, int segment
             if (segments == 0 && nseg > 1 && seg_chunks < 2) break;
             for (int c = 1; c >= 0; --c) {
                 if (c ? !try_coop : !try_wide) continue;
-                const double t = predicted_us(c != 0, BH, N, D, nseg, seg_chunks);
+                const double t = predicted_us(c != 0, BH, N, D, out16, nseg, seg_chunks);
                 if (!have || t < best * 0.98) {
                     have = true; best = t; best_coop = c != 0; best_nseg = nseg; best_chunks = seg_chunks;
                 }
@@ -261,7 +261,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dv, dtype, out_dtype == LEET_F32, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dv, dtype, out_dtype != LEET_F32, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -298,7 +298,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
 
     const bool coop = plan.coop;
     auto launch_states = [&]() {
-        return coop   ? leet::launch_fwd_bf16_coop_states(p, (int)BH, d, s)
+        return coop   ? leet::launch_fwd_16bit_coop_states(p, (int)BH, d, f16, s)
                : in16 ? leet::launch_fwd_16bit_states(pre, (int)BH, d, dv, f16, s)
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
@@ -306,7 +306,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
         return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk, p.state_step, d, dv, s);
     };
     auto launch_walk = [&]() {
-        return coop   ? leet::launch_fwd_bf16_coop_walk(p, (int)BH, d, s)
+        return coop   ? leet::launch_fwd_16bit_coop_walk(p, (int)BH, d, f16, out16, s)
                : in16 ? leet::launch_fwd_16bit_walk(p, (int)BH, d, dv, f16, out16, s)
                       : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
     };
@@ -401,7 +401,7 @@ size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtyp
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, r, dv, dtype, true, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, r, dv, dtype, false, segments, &plan)) return 0;
     return plan.ws_bytes;
 }
 
@@ -444,7 +444,7 @@ int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, in
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     if (!shape_ok(d, dtype, &status)) return status;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, d, dtype, true, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan((long)B * H, N, d, d, dtype, false, segments, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;
     if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
     return LEET_OK;

@@ -1,4 +1,5 @@
-// Column-split chunk-walk kernel for bf16 inputs (gfx950, v_mfma_f32_32x32x16_bf16).
+// Column-split chunk-walk kernel for bf16 or fp16 inputs (gfx950, v_mfma_f32_32x32x16_bf16 / _f16),
+// fp32 output or output in the input type.
 //
 // Same mathematics as the wide kernel in leet_fwd_16bit.hip -- Alg. 2 (Appendix B.2) with the
 // decaying mask of Eq. "BCMV" (Section 2.2) and the weight split of Alg. 4 (Appendix B.3):
@@ -25,7 +26,7 @@
 //   waves 6, 7   loaders: all global loads of the workgroup and the LDS writes of the tiles
 //   G4  S[dk tile][c] = gamma^L S + K^T (Gam V), A = K through transposing reads, B = the
 //       Gam-scaled V copy; the owner keeps its 32x32 fp32 tile in accumulators for the whole
-//       walk and publishes it as bf16 S^T[c][dk] for the G3 waves of the next chunk.
+//       walk and publishes it in the input type as S^T[c][dk] for the G3 waves of the next chunk.
 //
 // A compute unit accepts only so many outstanding vector-memory requests, and a wave that
 // issues one more stalls at that instruction until there is room; a wave that both loads and
@@ -72,8 +73,9 @@ struct CoopSmem {
 
 namespace coop {
 
-__device__ __forceinline__ bf16x8 frag16(const uint16_t* p) {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p));
+// MFMA operands travel as raw 128-bit registers (eight 16-bit elements)
+__device__ __forceinline__ u32x4 frag16(const uint16_t* p) {
+    return *reinterpret_cast<const u32x4*>(p);
 }
 
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element i%4 of the
@@ -86,22 +88,19 @@ __device__ __forceinline__ u32x2 lds_tr(const uint16_t* p) {
 
 // keys {k0..k0+3} and {k0+8..k0+11} of this lane's column: the order in which a 32x32
 // accumulator holds its rows (k0 = 16 f + 4 g)
-__device__ __forceinline__ bf16x8 frag_tr(const uint16_t* p, int row_stride) {
+__device__ __forceinline__ u32x4 frag_tr(const uint16_t* p, int row_stride) {
     u32x2 a = lds_tr(p), b = lds_tr(p + 8 * row_stride);
     u32x4 r = {a.x, a.y, b.x, b.y};
-    return __builtin_bit_cast(bf16x8, r);
-}
-
-// registers 8h .. 8h+7 of an accumulator tile -> bf16 operand
-__device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int h) {
-    bf16x8 r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (__bf16)acc[8 * h + e];
     return r;
 }
 
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+// registers 8h .. 8h+7 of an accumulator tile -> 16-bit operand
+template <typename E>
+__device__ __forceinline__ u32x4 pack_half(const f32x16& acc, int h) {
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = E::pack2(acc[8 * h + 2 * e], acc[8 * h + 2 * e + 1]);
+    return r;
 }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -114,9 +113,11 @@ __device__ __forceinline__ f32x16 zero16() {
 }  // namespace coop
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
-template <int D, bool kOut>
-__global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngroups, int map_mode) {
+// E: ElemBf16 or ElemF16 (input type).  kOut16: outputs in the input type instead of fp32.
+template <int D, bool kOut, typename E, bool kOut16>
+__global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ngroups, int map_mode) {
     using namespace coop;
+    auto mfma32 = [](u32x4 a, u32x4 b, f32x16 c) { return E::mfma32(a, b, c); };
     constexpr int NT = 512;        // threads: eight waves
     constexpr int NL = 128;        // loader threads (waves 6, 7)
     constexpr int SL = D / 32;     // column slices (workgroups) per sequence segment
@@ -163,7 +164,8 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     const uint16_t* qg = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
     const uint16_t* kg = reinterpret_cast<const uint16_t*>(p.k) + seq_off;
     const uint16_t* vg = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
-    float* og = static_cast<float*>(p.out) + seq_off;
+    float* og = static_cast<float*>(p.out) + seq_off;                       // fp32 output
+    uint16_t* og16 = static_cast<uint16_t*>(p.out) + seq_off;               // output in the input type
 
     {
         const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
@@ -190,8 +192,8 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
     // S^T[c][dk] in LDS: registers 8h..8h+7 are dk = 32 t + 16 h + 8 g + (0..7)
     const int st_wr_off = ln * RST + 32 * max(st_tile, 0) + 8 * g;  // + 16 h
     auto publish_state = [&](int buf) {
-        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off]) = __builtin_bit_cast(u32x4, pack_half(S, 0));
-        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 16]) = __builtin_bit_cast(u32x4, pack_half(S, 1));
+        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off]) = pack_half<E>(S, 0);
+        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 16]) = pack_half<E>(S, 1);
     };
     if (kOut && state_wave) publish_state(0);
 
@@ -259,15 +261,10 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             if (kOut) *reinterpret_cast<u32x4*>(&sm.v[vb][v_loff + 32 * m * RSV]) = st.v[m];
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
             u32x4 sc;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                bf16x2 pr;
-                pr[0] = (__bf16)(__uint_as_float(st.v[m][e] << 16) * v_scale[m]);
-                pr[1] = (__bf16)(__uint_as_float(st.v[m][e] & 0xffff0000u) * v_scale[m]);
-                sc[e] = __builtin_bit_cast(uint32_t, pr);
-            }
+            for (int e = 0; e < 4; ++e)
+                sc[e] = E::pack2(E::lo(st.v[m][e]) * v_scale[m], E::hi(st.v[m][e]) * v_scale[m]);
             *reinterpret_cast<u32x4*>(&sm.vs[vb][v_loff + 32 * m * RSV]) = sc;
         }
     };
@@ -311,8 +308,8 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
                 for (int s = 0; s < D / 16; ++s) acc = mfma32(frag16(ka + 16 * s), frag16(qa + 16 * s), acc);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
-                sm.pfrag[qb][w][0][l] = __builtin_bit_cast(u32x4, pack_half(acc, 0));
-                sm.pfrag[qb][w][1][l] = __builtin_bit_cast(u32x4, pack_half(acc, 1));
+                sm.pfrag[qb][w][0][l] = pack_half<E>(acc, 0);
+                sm.pfrag[qb][w][1][l] = pack_half<E>(acc, 1);
             }
             if (out_wave) {
                 if (t >= 1 && t <= n) {
@@ -322,12 +319,12 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
                     if (it_own == 0) {
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh)
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][0][hh][l]), o);
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), sm.pfrag[pb][0][hh][l], o);
                     } else {
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh) {
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][2][hh][l]), o);
-                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), __builtin_bit_cast(bf16x8, sm.pfrag[pb][1][hh][l]), o);
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), sm.pfrag[pb][2][hh][l], o);
+                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), sm.pfrag[pb][1][hh][l], o);
                         }
                     }
                     // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
@@ -356,13 +353,29 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
                 // once and must not displace Q and K, which the sibling slices re-read, from L2.
                 const int c = t - 2;
                 const int cshift = (c == n - 1) ? last_shift : 0;
-                float* oc = og + (size_t)(tok_begin + c * kChunk - cshift) * D + c0 + 4 * (l & 7);  // + row * D
-                const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
+                const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * D + c0;  // + row * D
+                if (!kOut16) {
+                    float* oc = og + tile_off + 4 * (l & 7);
+                    const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
-                    const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                    if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
+                    for (int m = 0; m < 8; ++m) {
+                        const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
+                        const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
+                        if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
+                    }
+                } else {
+                    // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
+                    uint16_t* oc = og16 + tile_off + 8 * (l & 3);
+                    const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 2) * 36 + 8 * (l & 3)];
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const int row = 16 * m + (l >> 2);  // row block m / 2
+                        const float* src = ot + (m >> 1) * (32 * 36) + (16 * (m & 1)) * 36;
+                        const f32x4 a = *reinterpret_cast<const f32x4*>(src);
+                        const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
+                        const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
+                        if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * D));
+                    }
                 }
             }
             if (state_wave && t < n) {
@@ -393,19 +406,26 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
         store_tiles(stg[0], 0);
         prefetch(stg[0], 2);
         __syncthreads();
-        // iteration t: chunk t+1 from its stage into LDS, the stage refilled with chunk t+3
+        // iteration t (t = 0 .. n-2): chunk t+1 from its stage into LDS, the stage refilled with
+        // chunk t+3.  The steady-state loop takes the two stages in turn with nothing conditional
+        // inside: the compiler counts outstanding loads along every path that reaches a wait, and
+        // a path on which the other stage's loads had not been issued would make it wait for all
+        // of them, which drains the prefetch once per chunk.
         auto step = [&](int t, Stage& nxt) {
-            if (t + 1 < n) {
-                store_tiles(nxt, t + 1);
-                prefetch(nxt, t + 3);
-            }
+            store_tiles(nxt, t + 1);
+            prefetch(nxt, t + 3);
             __syncthreads();
         };
-        for (int t = 0; t <= t_end; t += 2) {
+        int t = 0;
+        for (; t + 1 <= n - 2; t += 2) {
             step(t, stg[1]);
-            if (t + 1 > t_end) break;
             step(t + 1, stg[0]);
         }
+        if (t <= n - 2) {
+            step(t, stg[1]);
+            ++t;
+        }
+        for (; t <= t_end; ++t) __syncthreads();  // iterations that load nothing
     } else {
         __syncthreads();
         for (int t = 0; t <= t_end; ++t) iteration(t);
@@ -429,24 +449,31 @@ __global__ __launch_bounds__(512) void fwd_bf16_coop_kernel(FwdParams p, int ngr
 bool g_coop_consecutive_ids = false;
 
 namespace {
-template <int D, bool kOut>
+template <int D, bool kOut, typename E, bool kOut16>
 hipError_t launch_coop(const FwdParams& p, int BH, hipStream_t stream) {
     const int ngroups = BH * (kOut ? p.nseg : p.nseg - 1);
     if (ngroups <= 0) return hipSuccess;
     const int blocks = 8 * (D / 32) * ((ngroups + 7) / 8);
     const int map_mode = g_coop_consecutive_ids ? 1 : 0;
-    hipLaunchKernelGGL((fwd_bf16_coop_kernel<D, kOut>), dim3(blocks), dim3(512), 0, stream, p, ngroups, map_mode);
+    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, kOut, E, kOut16>), dim3(blocks), dim3(512), 0, stream, p, ngroups, map_mode);
     return hipGetLastError();
+}
+
+template <bool kOut, typename E, bool kOut16>
+hipError_t launch_coop_d(const FwdParams& p, int BH, int D, hipStream_t stream) {
+    return D == 64 ? launch_coop<64, kOut, E, kOut16>(p, BH, stream) : launch_coop<128, kOut, E, kOut16>(p, BH, stream);
 }
 }  // namespace
 
-hipError_t launch_fwd_bf16_coop_states(const FwdParams& p, int BH, int D, hipStream_t stream) {
+// D = 64 or 128 (square shapes); f16: fp16 instead of bf16 inputs; out16: output in the input type
+hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream) {
     if (p.nseg <= 1) return hipSuccess;
-    return D == 64 ? launch_coop<64, false>(p, BH, stream) : launch_coop<128, false>(p, BH, stream);
+    return f16 ? launch_coop_d<false, ElemF16, false>(p, BH, D, stream) : launch_coop_d<false, ElemBf16, false>(p, BH, D, stream);
 }
 
-hipError_t launch_fwd_bf16_coop_walk(const FwdParams& p, int BH, int D, hipStream_t stream) {
-    return D == 64 ? launch_coop<64, true>(p, BH, stream) : launch_coop<128, true>(p, BH, stream);
+hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream) {
+    if (f16) return out16 ? launch_coop_d<true, ElemF16, true>(p, BH, D, stream) : launch_coop_d<true, ElemF16, false>(p, BH, D, stream);
+    return out16 ? launch_coop_d<true, ElemBf16, true>(p, BH, D, stream) : launch_coop_d<true, ElemBf16, false>(p, BH, D, stream);
 }
 
 }  // namespace leet

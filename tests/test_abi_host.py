@@ -107,8 +107,8 @@ def test_kernel_choice_setter_and_plan_query(lib):
         assert b.query_plan(4, 16, 16384, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)            # inputs beyond the cache
         assert b.query_plan(8, 16, 16384, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # d = 64: two slices a sequence
         assert b.query_plan(8, 16, 4096, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)
-        assert b.query_plan(4, 16, 4096, 128, b.LEET_F32)[1] == b.KERNEL_WIDE                # bf16 only
-        assert b.query_plan(4, 16, 4096, 128, b.LEET_F16)[1] == b.KERNEL_WIDE
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_F32)[1] == b.KERNEL_WIDE                # 16-bit inputs only
+        assert b.query_plan(4, 16, 4096, 128, b.LEET_F16) == (1, b.KERNEL_COLUMN_SPLIT)         # both 16-bit types
         # a lone sequence: many short segments of the column-split kernel
         nseg, kern = b.query_plan(1, 1, 4096, 128, b.LEET_BF16)
         assert kern == b.KERNEL_COLUMN_SPLIT and 8 <= nseg <= 16

@@ -66,10 +66,13 @@ OPTION_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("kernel", ["auto", "wide", "column-split"])
 @pytest.mark.parametrize("shape", OPTION_SHAPES, ids=lambda s: "B%d_H%d_N%d_d%d_%s_out16%d_seg%d" % s)
-def test_fp16_inputs_and_16bit_outputs(B, shape):
+def test_fp16_inputs_and_16bit_outputs(B, shape, kernel):
+    """fp16 and bf16 inputs, fp32 output or output in the input type, through the planner's choice
+    and through each kernel family forced."""
     Bn, H, N, d, dtype, out16, segs = shape
-    say(f"case shape={shape}")
+    say(f"case shape={shape} kernel={kernel}")
     gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
     q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=2000 + N + d, gamma=gamma)
     rng = np.random.default_rng(N)
@@ -78,26 +81,27 @@ def test_fp16_inputs_and_16bit_outputs(B, shape):
     s_out = torch.empty_like(ds_in)
     q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
     odt = W.torch_dtype(dtype) if out16 else torch.float32
+    B.set_bf16_kernel({"auto": B.KERNEL_AUTO, "wide": B.KERNEL_WIDE, "column-split": B.KERNEL_COLUMN_SPLIT}[kernel])
+    try:
+        out = B.leet_attn_forward_v2(dq, dk, dv, dg, state_out=s_out, segments=segs, out_dtype=odt)
+        assert out.dtype == odt
+        ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+        check(to_np(out), ref, TOL[dtype], "zero state: out")
+        check(to_np(s_out), s_ref, TOL[dtype], "zero state: final state")
 
-    out = B.leet_attn_forward_v2(dq, dk, dv, dg, state_out=s_out, segments=segs, out_dtype=odt)
-    assert out.dtype == odt
-    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
-    check(to_np(out), ref, TOL[dtype], "zero state: out")
-    check(to_np(s_out), s_ref, TOL[dtype], "zero state: final state")
+        out2 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, state_out=s_out, segments=segs, out_dtype=odt)
+        ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+        check(to_np(out2), ref2, TOL[dtype], "with state_in: out")
+        check(to_np(s_out), s_ref2, TOL[dtype], "with state_in: final state")
 
-    out2 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, state_out=s_out, segments=segs, out_dtype=odt)
-    ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
-    check(to_np(out2), ref2, TOL[dtype], "with state_in: out")
-    check(to_np(s_out), s_ref2, TOL[dtype], "with state_in: final state")
-
-    if out16:
-        # the 16-bit output is the fp32 output of the same (wide) kernel, rounded to nearest even
-        B.set_bf16_kernel(B.KERNEL_WIDE)
-        try:
-            out32 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=segs)
-        finally:
-            B.set_bf16_kernel(B.KERNEL_AUTO)
-        assert torch.equal(out32.to(odt), out2), "16-bit output is not the rounded fp32 output"
+        if out16 and kernel != "auto":
+            # the 16-bit output is the fp32 output of the same kernel and plan, rounded to nearest even
+            fixed = segs or 2
+            o16 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=fixed, out_dtype=odt)
+            o32 = B.leet_attn_forward_v2(dq, dk, dv, dg, state_in=ds_in, segments=fixed)
+            assert torch.equal(o32.to(odt), o16), "16-bit output is not the rounded fp32 output"
+    finally:
+        B.set_bf16_kernel(B.KERNEL_AUTO)
 
 
 CAUSAL_SHAPES = [

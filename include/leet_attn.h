@@ -129,8 +129,7 @@ int leet_attn_forward_ex(const void *q, const void *k, const void *v, const floa
  *              that type, rounded to nearest even from the fp32 accumulators (halves the
  *              output traffic of an HBM-bound kernel)
  *   mask       a leet_mask
- * Any other combination returns LEET_ERR_UNSUPPORTED.  States stay fp32.  The column-split
- * kernel (leet_attn_set_bf16_kernel) is used only for bf16 in, fp32 out, decaying mask.
+ * Any other combination returns LEET_ERR_UNSUPPORTED.  States stay fp32.
  */
 int leet_attn_forward_v2(const void *q, const void *k, const void *v, const float *gamma, void *out,
                          const float *state_in, float *state_out,
@@ -173,6 +172,24 @@ int leet_attn_decode_step_rd(const void *q, const void *k, const void *v, const 
                              float *state_inout, float *out, int B, int H, int r, int dv, int dtype, int mask,
                              void *stream);
 size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtype, int segments);
+
+/*
+ * FleetAttention prefill: the operator as the sum over the rank of discounted cumulative sums,
+ * O = sum_j diag(b_j) lambda-cumsum(diag(c_j) V) (Section 3, Eq. "p"; Appendix C.1 for the decay),
+ * evaluated in column blocks (parallel) and row blocks (in order) with one carried vector per
+ * rank index, as Alg. 5 (Appendix B.4) lays it out.  Element-wise work on the vector ALUs only,
+ * no MFMA: like the row-based kernel it is an in-library comparison point (the paper's own
+ * measurements, Section 5.1 and Appendix E, have it slowest), not the fast path.
+ *   q, k   [B][H][N][r] of `dtype` (the paper's B and C)      v   [B][H][N][dv] of `dtype`
+ *   out    [B][H][N][dv] float
+ *   state_in, state_out   [B][H][r][dv] float or NULL: the carried vectors l^j entering the first
+ *          row block and leaving the last; they are the rows of the state the other kernels use
+ *   mask   a leet_mask (gamma may be NULL for LEET_MASK_CAUSAL: plain cumsum)
+ * Shapes as for leet_attn_forward_recurrent_rd.  Needs no workspace and no atomics.
+ */
+int leet_attn_forward_fleet(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                            const float *state_in, float *state_out,
+                            int B, int H, int N, int r, int dv, int dtype, int mask, void *stream);
 
 /* As leet_attn_decode_step_ex, with `dtype` also LEET_F16 and with a leet_mask. */
 int leet_attn_decode_step_v2(const void *q, const void *k, const void *v, const float *gamma,

@@ -78,8 +78,14 @@ def _lambda_cumsum(x: np.ndarray, lam: float) -> np.ndarray:
 
 
 def fleet(q, k, v, gamma) -> np.ndarray:
-    """Rank-by-rank form: sum over columns r of Q, K of diag(q_r) lambda-cumsum(diag(k_r) V)."""
-    q, k, v, gamma = _as4(q, k, v, gamma)
+    """Rank-by-rank form: sum over columns r of Q, K of diag(q_r) lambda-cumsum(diag(k_r) V).
+
+    Q and K are N x r, V is N x d (Section 2.2): the rank need not equal the value width."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64).reshape(-1)
+    assert q.ndim == 4 and q.shape == k.shape and v.shape[:3] == q.shape[:3] and gamma.shape[0] == q.shape[1]
     B, H, N, d = q.shape
     out = np.zeros_like(v)
     for b in range(B):

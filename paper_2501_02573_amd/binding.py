@@ -31,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_forward_recurrent",
     "leet_attn_forward_rd",
     "leet_attn_forward_recurrent_rd",
+    "leet_attn_forward_fleet",
     "leet_attn_decode_step_rd",
     "leet_attn_workspace_bytes_rd",
     "leet_attn_forward_profile",
@@ -74,6 +75,8 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_forward_rd.restype = i
     lib.leet_attn_forward_recurrent_rd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.leet_attn_forward_recurrent_rd.restype = i
+    lib.leet_attn_forward_fleet.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_fleet.restype = i
     lib.leet_attn_decode_step_rd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
     lib.leet_attn_decode_step_rd.restype = i
     lib.leet_attn_workspace_bytes_rd.argtypes = [i, i, i, i, i, i, i]
@@ -460,6 +463,25 @@ def leet_attn_forward_recurrent_rd(q, k, v, gamma: Optional[torch.Tensor], out: 
                                                 ctypes.c_void_p(_stream_ptr(dev)))
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_forward_recurrent_rd")
+    return out
+
+
+def leet_attn_forward_fleet(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                            state_in: Optional[torch.Tensor] = None,
+                            state_out: Optional[torch.Tensor] = None,
+                            mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """FleetAttention prefill (rank-sum of discounted cumulative sums); q, k [B, H, N, r], v [B, H, N, dv]."""
+    if out is None:
+        out = torch.empty(v.shape, dtype=torch.float32, device=v.device)
+    B, H, N, r, dv = _check_rd(q, k, v, gamma, out, False)
+    _check_states_rd(B, H, r, dv, state_in=state_in, state_out=state_out)
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_fleet(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                         _ptr(state_out), B, H, N, r, dv, _dtype_code(q), int(mask),
+                                         ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_fleet")
     return out
 
 

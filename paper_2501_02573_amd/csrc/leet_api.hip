@@ -21,6 +21,9 @@ hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float*
 hipError_t launch_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
                             const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
                             int elem, hipStream_t stream);
+hipError_t launch_fleet(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                        const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
+                        int elem, hipStream_t stream);
 hipError_t launch_decode(const void* q, const void* k, const void* v, const float* gamma, float* state,
                          float* out, int BH, int H, int D, int DV, int elem, bool stream_store,
                          hipStream_t stream);
@@ -352,6 +355,31 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     return rc;
 }
 
+// the two comparison kernels (row-based, FleetAttention) take the same arguments
+int forward_elementwise(bool fleet, const void* q, const void* k, const void* v, const float* gamma, float* out,
+                        const float* state_in, float* state_out, int B, int H, int N, int d, int dv,
+                        int dtype, int mask, void* stream) {
+    if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
+    if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
+    if (!q || !k || !v || !out || (!gamma && mask == LEET_MASK_DECAY)) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
+    int status = LEET_OK;
+    if (!shape_ok(d, dv, dtype, &status)) return status;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
+        !aligned16(state_out) || (reinterpret_cast<uintptr_t>(gamma) & 3u))
+        return LEET_ERR_INVALID_ARG;
+    const long BH = (long)B * H;
+    if (BH >= (1L << 31) / 8 || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
+    int dev = 0;
+    status = current_device(&dev);
+    if (status != LEET_OK) return status;
+    const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = fleet ? leet::launch_fleet(q, k, v, gamma, out, state_in, state_out, (int)BH, H, N, d, dv, elem, s)
+                         : leet::launch_recurrent(q, k, v, gamma, out, state_in, state_out, (int)BH, H, N, d, dv, elem, s);
+    return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -412,24 +440,13 @@ size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segm
 int leet_attn_forward_recurrent_rd(const void* q, const void* k, const void* v, const float* gamma, float* out,
                                    const float* state_in, float* state_out, int B, int H, int N, int d, int dv,
                                    int dtype, int mask, void* stream) {
-    if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
-    if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
-    if (!q || !k || !v || !out || (!gamma && mask == LEET_MASK_DECAY)) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
-    int status = LEET_OK;
-    if (!shape_ok(d, dv, dtype, &status)) return status;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
-        !aligned16(state_out) || (reinterpret_cast<uintptr_t>(gamma) & 3u))
-        return LEET_ERR_INVALID_ARG;
-    const long BH = (long)B * H;
-    if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
-    int dev = 0;
-    status = current_device(&dev);
-    if (status != LEET_OK) return status;
-    const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
-    hipError_t e = leet::launch_recurrent(q, k, v, gamma, out, state_in, state_out, (int)BH, H, N, d, dv, elem,
-                                          static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+    return forward_elementwise(false, q, k, v, gamma, out, state_in, state_out, B, H, N, d, dv, dtype, mask, stream);
+}
+
+int leet_attn_forward_fleet(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                            const float* state_in, float* state_out, int B, int H, int N, int r, int dv,
+                            int dtype, int mask, void* stream) {
+    return forward_elementwise(true, q, k, v, gamma, out, state_in, state_out, B, H, N, r, dv, dtype, mask, stream);
 }
 
 int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,

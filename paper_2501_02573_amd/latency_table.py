@@ -12,9 +12,10 @@ Rows are this library's methods:
                                lightningAttention-2 rows play), fp32 output
   chunked bf16, bf16 out       the same with 16-bit output
   row-based bf16               the token-by-token recursion (the role of causal-dot-product)
+  FleetAttention bf16          the rank-sum of discounted cumulative sums (Alg. 5), element-wise
   chunked bf16, dim 256        rank 128 with value width 256, the shape of the paper's usage example
-The paper's own lightningAttention-2 row (one A6000; other hardware, so context only) is printed
-underneath the tables with the decaying mask.
+The paper's own lightningAttention-2 row (Section 5.1, decaying mask) and FleetAttention row
+(Appendix E; both masks) are printed underneath: one A6000, other hardware, so context only.
 
 PyTorch is used for device memory, random inputs and events; all arithmetic of the operator
 runs in the library's kernels.
@@ -31,10 +32,15 @@ REPS = 15
 
 # Section 5.1, tables for batch 1 and batch 16 (seconds, one A6000, heads/dim/dtype unstated):
 # row "LA" (lightningAttention-2, Triton).  None = out of memory there.
+# Appendix E, runtime table of FleetAttention: row "FA" (Triton, atomic rank sum).
 PAPER_ROWS = {
     # (batch, decay): {row: values over N_LIST}
-    (1, True): {"LA (paper, A6000)": (1.27e-4, 1.96e-4, 7.49e-4, 2.9e-3, 4.51e-3, 9.08e-3, 4.14e-2)},
-    (16, True): {"LA (paper, A6000)": (6.52e-4, 2.57e-3, 1.05e-2, 4.28e-2, 6.49e-2, 1.34e-1, None)},
+    (1, True): {"LA (paper, A6000)": (1.27e-4, 1.96e-4, 7.49e-4, 2.9e-3, 4.51e-3, 9.08e-3, 4.14e-2),
+                "FA (paper, A6000)": (1.26e-3, 5.49e-3, 2.71e-2, 1.14e-1, 1.78e-1, 3.59e-1, 1.42)},
+    (1, False): {"FA (paper, A6000)": (1.26e-3, 5.46e-3, 2.72e-2, 1.13e-1, 1.77e-1, 3.58e-1, 1.41)},
+    (16, True): {"LA (paper, A6000)": (6.52e-4, 2.57e-3, 1.05e-2, 4.28e-2, 6.49e-2, 1.34e-1, None),
+                 "FA (paper, A6000)": (1.85e-2, 7.49e-2, 3.90e-1, 1.48, 2.32, 4.65, None)},
+    (16, False): {"FA (paper, A6000)": (1.85e-2, 7.42e-2, 3.92e-1, 1.48, 2.31, 4.63, None)},
 }
 
 
@@ -42,6 +48,7 @@ def _methods(torch, binding):
     bf16, f16, f32 = torch.bfloat16, torch.float16, torch.float32
     fwd = binding.leet_attn_forward_v2
     rec = binding.leet_attn_forward_recurrent
+    flt = binding.leet_attn_forward_fleet
     frd = binding.leet_attn_forward_rd
     # (name, input dtype, output dtype, value width, call)
     return (
@@ -50,6 +57,7 @@ def _methods(torch, binding):
         ("chunked fp32", f32, f32, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
         ("chunked bf16, bf16 out", bf16, bf16, DIM, lambda q, k, v, g, o, m: fwd(q, k, v, g, out=o, mask=m)),
         ("row-based bf16", bf16, f32, DIM, lambda q, k, v, g, o, m: rec(q, k, v, g, out=o, mask=m)),
+        ("FleetAttention bf16", bf16, f32, DIM, lambda q, k, v, g, o, m: flt(q, k, v, g, out=o, mask=m)),
         ("chunked bf16, dim 256", bf16, f32, 2 * DIM, lambda q, k, v, g, o, m: frd(q, k, v, g, out=o, mask=m)),
     )
 

@@ -262,6 +262,52 @@ def test_row_based_prefill_kernel(B, shape):
     assert max_rel_err(to_np(out4), to_np(out)) <= TOL[dtype]
 
 
+# ---------------------------------------------------------------- FleetAttention (Eq. "p", Alg. 5 on the GPU)
+FLEET_SHAPES = [
+    # B, H, N, r, dv, dtype
+    (1, 1, 1, 64, 64, "f32"),
+    (2, 3, 31, 64, 64, "bf16"),
+    (1, 2, 32, 128, 128, "f32"),
+    (2, 2, 33, 128, 128, "f16"),
+    (1, 5, 777, 128, 128, "bf16"),
+    (2, 4, 1000, 64, 64, "f32"),
+    (1, 3, 100, 128, 256, "bf16"),
+    (2, 2, 65, 128, 256, "f16"),
+]
+
+
+@pytest.mark.parametrize("shape", FLEET_SHAPES, ids=lambda s: "B%d_H%d_N%d_r%d_dv%d_%s" % s)
+def test_fleet_attention_kernel(B, shape):
+    """fp32 element-wise arithmetic on exactly converted inputs: far inside every input-type bound.
+    Compared with the oracle's recurrence (outputs and carried vectors = state rows) and, at the
+    small sizes, with the oracle's own rank-sum-of-cumsums form."""
+    Bn, H, N, r, dv, dtype = shape
+    say(f"case fleet shape={shape}")
+    gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
+    q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N, r, dv, dtype, seed=5000 + N + r, gamma=gamma)
+    rng = np.random.default_rng(N)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, r, dv)) * 0.1).astype(np.float32))
+    dq, dk, dv_, dg, ds = dev(q, k, v, gamma, s_in)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (q, k, v, gamma))
+    s_out = torch.empty_like(ds)
+    out = B.leet_attn_forward_fleet(dq, dk, dv_, dg, state_out=s_out)
+    ref, s_ref = oracle.recurrent(q64, k64, v64, g64)
+    check(to_np(out), ref, 1e-5, "zero carry: out")
+    check(to_np(s_out), s_ref, 1e-5, "zero carry: carried vectors after the last block")
+    if N <= 100:
+        check(to_np(out), oracle.fleet(q64, k64, v64, g64), 1e-5, "zero carry: out vs the oracle's rank-sum form")
+    out2 = B.leet_attn_forward_fleet(dq, dk, dv_, dg, state_in=ds, state_out=ds)   # in place
+    ref2, s_ref2 = oracle.recurrent(q64, k64, v64, g64, state_in=W.to_f64(s_in))
+    check(to_np(out2), ref2, 1e-5, "with carry in: out")
+    check(to_np(ds), s_ref2, 1e-5, "with carry in: carried vectors (in place)")
+    out3 = B.leet_attn_forward_fleet(dq, dk, dv_, None, mask=B.LEET_MASK_CAUSAL)
+    ref3, _ = oracle.recurrent(q64, k64, v64, np.ones(H))
+    check(to_np(out3), ref3, 1e-5, "0/1 mask (plain cumsum): out")
+    # the chunked path agrees with it to the chunked path's own tolerance
+    out4 = B.leet_attn_forward_rd(dq, dk, dv_, dg)
+    assert max_rel_err(to_np(out4), to_np(out)) <= TOL[dtype]
+
+
 # ---------------------------------------------------------------- rank 128, value width 256 (the paper's usage example)
 RD_SHAPES = [
     # B, H, N, dtype, 16-bit output, segments

@@ -245,6 +245,22 @@ def test_fleet_and_recursion_identities():
         assert max_rel_err(oracle.recursion(q, k, v, gamma, base=base), ref) < 1e-12
 
 
+def test_fleet_identity_with_rank_different_from_width():
+    """Eq. p for B, C of width r and V of width d != r (Section 2.2) against Eq. BCMV written out."""
+    rng = np.random.default_rng(17)
+    Bn, H, N, r, d = 1, 2, 23, 5, 9
+    q, k = rng.standard_normal((Bn, H, N, r)), rng.standard_normal((Bn, H, N, r))
+    v = rng.standard_normal((Bn, H, N, d))
+    gamma = np.array([0.7, 1.0])
+    ref = np.zeros_like(v)
+    for h in range(H):
+        for i in range(N):
+            for j in range(i + 1):
+                ref[0, h, i] += gamma[h] ** (i - j) * (q[0, h, i] @ k[0, h, j]) * v[0, h, j]
+    assert max_rel_err(oracle.fleet(q, k, v, gamma), ref) < 1e-12
+    assert max_rel_err(oracle.quadratic(q, k, v, gamma), ref) < 1e-12
+
+
 def test_state_carry_prefill_then_decode():
     """Splitting a sequence: recurrent(first part) -> state -> recurrent/decode(rest) equals one pass."""
     B, H, N, d = 2, 2, 40, 8

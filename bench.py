@@ -37,6 +37,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector ALUs, published (256 CUs x 4 SIMDs x 2.4 GHz x 64 flop/clk with packed fp32)
 
 
 def parse_args():
@@ -324,8 +325,33 @@ def main():
             "streaming_stores": {"us_per_step": ms5s * 1e3, "achieved_GBps": b5 / (ms5s * 1e-3) / 1e9,
                                  "hbm_frac": b5 / (ms5s * 1e-3) / 1e9 / HBM_PEAK_GBS},
         }
-        result["extra"] = extra
         del S, qkv, o, cold
+
+        # the two element-wise comparison kernels on the headline workload (vector ALUs only):
+        # 3 multiply-adds = 5 flops per (token, rank index, value column)
+        q3, k3, v3, g3 = (t.to(dev) for t in W.make_forward_inputs(cfg))
+        o3 = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
+        alu_flops = 5.0 * cfg.B * cfg.H * cfg.N * cfg.d * cfg.d
+        extra["elementwise_methods"] = {"workload": cfg.name, "flops_per_call": alu_flops}
+        for name, fn in (("row_based", binding.leet_attn_forward_recurrent), ("fleet_attention", binding.leet_attn_forward_fleet)):
+            settle(torch)
+            for _ in range(5):
+                fn(q3, k3, v3, g3, out=o3)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(20):
+                fn(q3, k3, v3, g3, out=o3)
+            e1.record()
+            torch.cuda.synchronize()
+            ms_e = e0.elapsed_time(e1) / 20
+            extra["elementwise_methods"][name] = {
+                "ms_per_call": ms_e, "tokens_per_s": tokens / (ms_e * 1e-3),
+                "roofline": {"kernel": "elementwise_kernel<128,128,bf16,16,%s>" % ("rank-major" if name == "fleet_attention" else "token-major"),
+                             "bound": "alu", "achieved": alu_flops / (ms_e * 1e-3) / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                             "unit": "TFLOP/s", "frac": alu_flops / (ms_e * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, "traffic": None},
+            }
+        del q3, k3, v3, o3
+        result["extra"] = extra
 
     # ---------------- CPU baseline: the oracle as it stands, on this host's cores
     if not args.no_cpu_baseline:

@@ -59,12 +59,16 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 template <int D>
 struct CoopSmem {
     static constexpr int RSQ = D + 8;   // Q, K row stride (elements): 16-byte row reads spread over the banks
-    static constexpr int RSV = 48;      // V slice: 32 columns + pad; 4 rows x 32 B of a transposing read stay apart
+    // V slice, 32 columns, unpadded: the 4 rows x 32 B that 32 lanes of a transposing read touch
+    // are then consecutive (4 x 16 banks).  The Gam-scaled copy is read four rows apart (G4), so its
+    // rows are padded to 40 elements: rows 0, 4, 8, 12 start 16 banks apart.
+    static constexpr int RSV = 32;
+    static constexpr int RSVS = 40;
     static constexpr int RST = D + 8;   // S^T[c][dk]
     uint16_t q[2][kChunk * RSQ];
     uint16_t k[2][kChunk * RSQ];
     uint16_t v[3][kChunk * RSV];
-    uint16_t vs[3][kChunk * RSV];       // Gam V: row j scaled by gamma^(63-j)
+    uint16_t vs[3][kChunk * RSVS];      // Gam V: row j scaled by gamma^(63-j)
     u32x4 pfrag[2][3][2][64];           // masked P^T tiles as B operands: [buffer][tile][register half][lane]
     uint16_t st[2][32 * RST];
     float obuf[2][2][32 * 36];          // finished O tiles on their way out: [buffer][row block][row][column], padded rows
@@ -86,10 +90,12 @@ __device__ __forceinline__ u32x2 lds_tr(const uint16_t* p) {
     return __builtin_bit_cast(u32x2, r);
 }
 
-// keys {k0..k0+3} and {k0+8..k0+11} of this lane's column: the order in which a 32x32
-// accumulator holds its rows (k0 = 16 f + 4 g)
-__device__ __forceinline__ u32x4 frag_tr(const uint16_t* p, int row_stride) {
-    u32x2 a = lds_tr(p), b = lds_tr(p + 8 * row_stride);
+// Two transposing reads make one operand.  G2 pairs V with P^T accumulators and so reads keys
+// {k0..k0+3} and {k0+8..k0+11} of this lane's column, the order in which a 32x32 accumulator
+// holds its rows (k0 = 16 f + 4 g; second_off = 8 rows).  G4 takes both operands from such reads
+// and may order the keys as it likes: it reads rows four apart (second_off = 32 rows).
+__device__ __forceinline__ u32x4 frag_tr(const uint16_t* p, int second_off) {
+    u32x2 a = lds_tr(p), b = lds_tr(p + second_off);
     u32x4 r = {a.x, a.y, b.x, b.y};
     return r;
 }
@@ -125,7 +131,7 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
     constexpr int PR = D / 8;      // 16-byte pieces per Q/K row
     constexpr int QPL = kChunk * PR / NL;  // Q (and K) pieces per loader thread per chunk
     constexpr int RPL = NL / PR;   // rows between two pieces of one loader thread
-    constexpr int RSQ = CoopSmem<D>::RSQ, RSV = CoopSmem<D>::RSV, RST = CoopSmem<D>::RST;
+    constexpr int RSQ = CoopSmem<D>::RSQ, RSV = CoopSmem<D>::RSV, RSVS = CoopSmem<D>::RSVS, RST = CoopSmem<D>::RST;
     __shared__ __attribute__((aligned(16))) CoopSmem<D> sm;
 
     // Block -> (sequence segment, column slice).  Consecutive block ids go round-robin over
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
     const int qk_row = lt / PR, qk_cc = lt % PR;
     const int v_row = lt >> 2, v_cc = lt & 3;
     const int qk_loff = qk_row * RSQ + qk_cc * 8;
-    const int v_loff = v_row * RSV + v_cc * 8;
+    const int v_loff = v_row * RSV + v_cc * 8, vs_loff = v_row * RSVS + v_cc * 8;
 
     // Two register stages: chunk c travels in stage c & 1 from the moment its loads are issued
     // (two chunks ahead of the iteration that writes it to LDS) until it is written.  (A third
@@ -265,7 +271,7 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 sc[e] = E::pack2(E::lo(st.v[m][e]) * v_scale[m], E::hi(st.v[m][e]) * v_scale[m]);
-            *reinterpret_cast<u32x4*>(&sm.vs[vb][v_loff + 32 * m * RSV]) = sc;
+            *reinterpret_cast<u32x4*>(&sm.vs[vb][vs_loff + 32 * m * RSVS]) = sc;
         }
     };
 
@@ -285,7 +291,12 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
     const int row_off = ln * RSQ + 8 * g;  // 16-byte row fragments of Q, K: + 32 tile RSQ + 16 s
     // transposing reads: lane supplies row 4g + s16/4 (+ 16 f, + 8 for the second half) and four columns
     const int tr_off_v = (4 * g + (s16 >> 2)) * RSV + 16 * half + 4 * (s16 & 3);
-    const int tr_off_k = (4 * g + (s16 >> 2)) * RSQ + 32 * max(st_tile, 0) + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);
+    // G4 contracts keys f + 4u (u = 0..15) in its MFMA number f: one transposing read then touches
+    // rows four apart, which the Q/K row stride (4 banks per row) spreads over all banks; with
+    // consecutive rows the 64-byte pieces of eight rows would overlap four deep.
+    const int tr_row4 = 16 * g + 4 * (s16 >> 2);
+    const int tr_off_k = tr_row4 * RSQ + 32 * max(st_tile, 0) + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);
+    const int tr_off_vs = tr_row4 * RSVS + 16 * half + 4 * (s16 & 3);
     const int st_rd_off = ln * RST + 8 * g;  // + 16 s
 
     f32x16 o = zero16();  // output waves: the row block of the chunk in progress
@@ -319,12 +330,12 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
                     if (it_own == 0) {
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh)
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), sm.pfrag[pb][0][hh][l], o);
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, 8 * RSV), sm.pfrag[pb][0][hh][l], o);
                     } else {
 #pragma unroll
                         for (int hh = 0; hh < 2; ++hh) {
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, RSV), sm.pfrag[pb][2][hh][l], o);
-                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, RSV), sm.pfrag[pb][1][hh][l], o);
+                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, 8 * RSV), sm.pfrag[pb][2][hh][l], o);
+                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, 8 * RSV), sm.pfrag[pb][1][hh][l], o);
                         }
                     }
                     // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
@@ -384,10 +395,10 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
 #pragma unroll
                 for (int r = 0; r < 16; ++r) S[r] *= gl;
                 const uint16_t* k_tr = &sm.k[qb][tr_off_k];
-                const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_v];
+                const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
-                    S = mfma32(frag_tr(k_tr + 16 * f * RSQ, RSQ), frag_tr(vs_tr + 16 * f * RSV, RSV), S);
+                    S = mfma32(frag_tr(k_tr + f * RSQ, 32 * RSQ), frag_tr(vs_tr + f * RSVS, 32 * RSVS), S);
                 if (kOut) publish_state((t + 1) & 1);
             }
         }

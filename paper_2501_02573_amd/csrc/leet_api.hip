@@ -84,10 +84,10 @@ struct CostModel {
     double wide_crowded;                        // transfer-time factor with more wide workgroups than CUs
     int wide_slots;                             // wide workgroups resident on the device
 };
-constexpr CostModel kCost128 = {2.589, 0.847, 0.908, 0.410, 8.0e6, 6.497e6, 6.056e6, 4.554e6,
-                                4.91, 11.32, 0.351, 2.204, 2.0, 1.243, 512};
-constexpr CostModel kCost64 = {1.847, 0.509, 0.645, 0.357, 7.487e6, 6.026e6, 8.0e6, 4.833e6,
-                               4.21, 10.37, 0.347, 2.632, 2.139, 1.135, 1024};
+constexpr CostModel kCost128 = {2.524, 0.801, 0.871, 0.373, 8.0e6, 6.470e6, 6.357e6, 5.550e6,
+                                5.27, 11.63, 0.348, 2.131, 2.0, 1.217, 512};
+constexpr CostModel kCost64 = {1.812, 0.452, 0.614, 0.303, 7.621e6, 6.056e6, 8.0e6, 5.809e6,
+                               4.41, 10.60, 0.345, 2.419, 2.286, 1.131, 1024};
 constexpr double kOneKernelFloorUs = 11.0;    // shortest call seen end to end, one and three kernels
 constexpr double kThreeKernelFloorUs = 17.0;
 constexpr int kCoopSlots = 256;               // one column-split workgroup per compute unit

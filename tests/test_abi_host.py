@@ -156,6 +156,38 @@ def test_planner_against_measured_sweep(lib):
     assert sum(ratios) / len(ratios) <= 1.01
 
 
+def test_planner_invariants_on_random_shapes(lib):
+    """Whatever the cost model prefers, a plan is well-formed: between 1 and ceil(N/64) segments,
+    a caller's segment count honoured up to rounding, and a workspace of one state per segment
+    boundary (two on the wide 16-bit path when it computes them on half-segments)."""
+    import random
+    from paper_2501_02573_amd import binding as b
+    rng = random.Random(7)
+    for _ in range(400):
+        d = rng.choice((64, 128))
+        dtype = rng.choice((b.LEET_F32, b.LEET_BF16, b.LEET_F16))
+        B, H = rng.randint(1, 6), rng.randint(1, 48)
+        N = rng.choice((1, 63, 64, 65, 500, 1000, 4096, 5000, 33000, 100000, rng.randint(1, 200000)))
+        segs = rng.choice((0, 0, 0, 1, 2, 3, 5, 8, 100))
+        nchunks = -(-N // 64)
+        nseg, kern = b.query_plan(B, H, N, d, dtype, segs)
+        assert 1 <= nseg <= nchunks, (B, H, N, d, dtype, segs, nseg)
+        if segs:
+            want = min(segs, nchunks)
+            seg_chunks = -(-nchunks // want)
+            assert nseg == -(-nchunks // seg_chunks)
+        if dtype == b.LEET_F32:
+            assert kern == b.KERNEL_WIDE
+        ws = b.workspace_bytes(B, H, N, d, dtype, segs)
+        state = B * H * d * d * 4
+        assert ws % state == 0
+        slots = ws // state
+        if kern == b.KERNEL_COLUMN_SPLIT or dtype == b.LEET_F32:
+            assert slots == nseg - 1
+        else:
+            assert slots in (nseg - 1, 2 * (nseg - 1))
+
+
 def test_binding_rejects_cpu_tensors(lib):
     import torch
     from paper_2501_02573_amd import binding as b

@@ -44,7 +44,7 @@ constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;  // MI355X Infinity Cache
 
-// Kernel choice for bf16 prefill: a leet_bf16_kernel value; LEET_KERNEL_AUTO unless the caller sets one.
+// Kernel choice for 16-bit prefill (bf16 and fp16; the name is historical): a leet_bf16_kernel value.
 std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
 
 // Decode-state store policy: a leet_decode_store value.

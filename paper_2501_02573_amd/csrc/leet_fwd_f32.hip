@@ -1,6 +1,6 @@
 // Chunk-walk kernel for fp32 inputs (gfx950, v_mfma_f32_16x16x4_f32: true fp32 products).
 //
-// Same algorithm as the bf16 kernel: one workgroup per segment of a (batch, head) sequence
+// Same algorithm as the wide 16-bit kernel: one workgroup per segment of a (batch, head) sequence
 // walks 64-token chunks (Alg. 2, Appendix B.2, with the decaying mask of Eq. "BCMV" and the
 // weight split of Alg. 4, Appendix B.3):
 //
@@ -8,7 +8,7 @@
 //     S_{t+1} = gamma^L S_t + (Gam K_t)^T V_t                Lam = diag(gamma^(i+1)), Gam = diag(gamma^(L-1-j))
 //
 // fp32 MFMA is 16 times slower than bf16 MFMA, so this kernel is bound by MFMA issue and
-// latency, not by HBM; the work is therefore cut finer than in the bf16 kernel: wave w owns
+// latency, not by HBM; the work is therefore cut finer than in the 16-bit kernels: wave w owns
 // 16 value columns [16w, 16w+16) of O and of the state S (d/16 waves per workgroup), and all
 // products are 16x16x4 tiles.
 //

@@ -20,9 +20,13 @@
 //                    (tiles (jt,it) = (0,0), (1,1), (0,1)); after that G4 for state tile n
 //   waves 3, 4   G3  O^T[c][i] = S^T Q^T for row block it = w-3 (S^T from LDS st[c][dk]),
 //                    rows scaled by gamma^(i+1); one iteration later G2: O^T += V^T P^T
-//                    (V through transposing LDS reads, P from pfrag); store
-//   wave  5      G4  for state tile 3 (d = 128 only); stores the finished O tiles, which the
-//                    output waves hand over through LDS, in whole 128-byte row pieces
+//                    (V through transposing LDS reads, P from pfrag), then the tile goes to
+//                    LDS for the store wave.  Wave 3, whose row block has one score tile to
+//                    fold in against wave 4's two, also owns state tile 3 (d = 128 only)
+//   wave  5      stores the finished O tiles in whole row pieces (and nothing else: its stores
+//                    queue behind the loaders' loads in the compute unit's one vector-memory
+//                    pipeline, which with 36 KB loaded and 8 KB stored per chunk is what the
+//                    iteration time comes down to)
 //   waves 6, 7   loaders: all global loads of the workgroup and the LDS writes of the tiles
 //   G4  S[dk tile][c] = gamma^L S + K^T (Gam V), A = K through transposing reads, B = the
 //       Gam-scaled V copy; the owner keeps its 32x32 fp32 tile in accumulators for the whole
@@ -50,6 +54,8 @@
 // Outputs are accumulated transposed (lane = token): Lam is one scalar per lane and a lane
 // stores 16 contiguous bytes.  A ragged last chunk is right-aligned in the tile (rows 64-L..
 // hold the tokens), which keeps every decay weight chunk-independent.
+#include <type_traits>
+
 #include "leet_common.hpp"
 
 namespace leet {
@@ -120,8 +126,14 @@ __device__ __forceinline__ f32x16 zero16() {
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
 // E: ElemBf16 or ElemF16 (input type).  kOut16: outputs in the input type instead of fp32.
-constexpr int kCoopLoaderWaves = 2;   // 2 or 4
-constexpr int kCoopStages = 2;        // register stages per loader thread (2 or 3)
+#ifndef LEET_COOP_LW
+#define LEET_COOP_LW 2
+#endif
+#ifndef LEET_COOP_NS
+#define LEET_COOP_NS 2
+#endif
+constexpr int kCoopLoaderWaves = LEET_COOP_LW;
+constexpr int kCoopStages = LEET_COOP_NS;
 constexpr int kCoopThreads = 384 + 64 * kCoopLoaderWaves;
 
 template <int D, bool kOut, typename E, bool kOut16>
@@ -161,9 +173,9 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // ---- roles
     const bool score_wave = kOut && w < 3;                       // G1 tile n = w
     const bool out_wave = kOut && (w == 3 || w == 4);            // output row block it = w - 3
-    const int st_tile = (w < 3) ? w : (w == 5 ? 3 : -1);         // state tile owned (G4), if it exists
+    const int st_tile = (w < 4) ? w : -1;                        // state tile owned (G4), if it exists: waves 0..2 and output wave 3
     const bool state_wave = st_tile >= 0 && st_tile < DT;
-    const bool store_wave = kOut && w == 5;                      // writes the finished O tiles to global memory
+    const bool store_wave = kOut && w == 5;                      // writes the finished O tiles to global memory, nothing else
     const bool loader = w >= 6;
     const int it_own = w - 3;
     const int lt = tid - (NT - NL);                              // loader thread index
@@ -217,12 +229,10 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     const int qk_loff = qk_row * RSQ + qk_cc * 8;
     const int v_loff = v_row * RSV + v_cc * 8, vs_loff = v_row * RSVS + v_cc * 8;
 
-    // NS register stages: chunk c travels in stage c % NS from the moment its loads are issued
-    // (NS chunks ahead of the iteration that writes it to LDS) until it is written.  Two loader
-    // waves with two stages are the default; four loader waves with three stages (108 KB in
-    // flight per compute unit instead of 72 KB) measured the same on the same device, as did
-    // the kernel with its loads switched off altogether minus 10 us: the walk is bound by the
-    // compute waves' chain of LDS reads, MFMAs and LDS writes between two barriers, not by the loads.
+    // Two register stages: chunk c travels in stage c & 1 from the moment its loads are issued
+    // (two chunks ahead of the iteration that writes it to LDS) until it is written.  (A third
+    // stage measured no faster: the loaders are bound by the rate at which one compute unit
+    // can pull data through its vector memory path, not by latency.)
     struct Stage {
         u32x4 q[QPL], k[QPL], v[VPL];
     };
@@ -308,110 +318,162 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     const int tr_off_vs = tr_row4 * RSVS + 16 * half + 4 * (s16 & 3);
     const int st_rd_off = ln * RST + 8 * g;  // + 16 s
 
-    f32x16 o = zero16();  // output waves: the row block of the chunk in progress
+    // ---- iteration t of the pipeline (t = 0 .. t_end), one body per role.  Each body is
+    // straight-line code that first issues every LDS read the iteration needs and then runs its
+    // MFMAs back to back, so that the reads of one product are in flight under the MFMAs of the
+    // other; the role and edge conditions are resolved outside (tags and peeled iterations).
 
-    // ---- iteration t of the pipeline (t = 0 .. t_end), compute waves
-    auto iteration = [&](int t) {
-        {
-            const int qb = t & 1;
-            const uint16_t* q_row = &sm.q[qb][row_off];
-            const uint16_t* k_row = &sm.k[qb][row_off];
-            const int shift = (t == n - 1) ? last_shift : 0;
-
-            if (score_wave && t < n) {
-                // G1: score tile n = w, (jt, it) = (0,0), (1,1), (0,1)
-                const int jt = (w == 1) ? 1 : 0, it = (w == 0) ? 0 : 1;
-                const uint16_t* ka = k_row + 32 * jt * RSQ;
-                const uint16_t* qa = q_row + 32 * it * RSQ;
-                f32x16 acc = zero16();
+    // Score and state waves, chunk t: G1 (score tile w -> pfrag) and G4 (state tile st_tile).
+    auto score_state = [&](int t, auto do_g1, auto do_g4) {
+        constexpr bool kG1 = decltype(do_g1)::value, kG4 = decltype(do_g4)::value;
+        const int qb = t & 1;
+        const int shift = (t == n - 1) ? last_shift : 0;
+        u32x4 kf[D / 16], qf[D / 16], ak[4], bv[4];
+        if (kG1) {
+            const int jt = (w == 1) ? 1 : 0, it = (w == 0) ? 0 : 1;  // tiles (0,0), (1,1), (0,1)
+            const uint16_t* ka = &sm.k[qb][row_off + 32 * jt * RSQ];
+            const uint16_t* qa = &sm.q[qb][row_off + 32 * it * RSQ];
 #pragma unroll
-                for (int s = 0; s < D / 16; ++s) acc = mfma32(frag16(ka + 16 * s), frag16(qa + 16 * s), acc);
+            for (int s = 0; s < D / 16; ++s) { kf[s] = frag16(ka + 16 * s); qf[s] = frag16(qa + 16 * s); }
+        }
+        if (kG4) {
+            const uint16_t* k_tr = &sm.k[qb][tr_off_k];
+            const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
-                sm.pfrag[qb][w][0][l] = pack_half<E>(acc, 0);
-                sm.pfrag[qb][w][1][l] = pack_half<E>(acc, 1);
-            }
-            if (out_wave) {
-                if (t >= 1 && t <= n) {
-                    // finish chunk t-1: G2, O^T += V^T P^T over the score tiles of this row block; store
-                    const int pb = (t - 1) & 1;
-                    const uint16_t* v_tr = &sm.v[(t - 1) % 3][tr_off_v];
-                    if (it_own == 0) {
-#pragma unroll
-                        for (int hh = 0; hh < 2; ++hh)
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, 8 * RSV), sm.pfrag[pb][0][hh][l], o);
-                    } else {
-#pragma unroll
-                        for (int hh = 0; hh < 2; ++hh) {
-                            o = mfma32(frag_tr(v_tr + 16 * hh * RSV, 8 * RSV), sm.pfrag[pb][2][hh][l], o);
-                            o = mfma32(frag_tr(v_tr + 16 * (2 + hh) * RSV, 8 * RSV), sm.pfrag[pb][1][hh][l], o);
-                        }
-                    }
-                    // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
-                    float* ot = &sm.obuf[qb][it_own][ln * 36 + 4 * g];
-#pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
-                        *reinterpret_cast<f32x4*>(ot + 8 * qd) = val;
-                    }
-                }
-                if (t < n) {
-                    // start chunk t: G3, O^T = S^T Q^T for row block it_own, rows scaled by gamma^(i+1)
-                    const uint16_t* st_rd = &sm.st[qb][st_rd_off];
-                    const uint16_t* qa = q_row + 32 * it_own * RSQ;
-                    o = zero16();
-#pragma unroll
-                    for (int s = 0; s < D / 16; ++s) o = mfma32(frag16(st_rd + 16 * s), frag16(qa + 16 * s), o);
-                    const float lam = shift ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[r] *= lam;
-                }
-            }
-            if (store_wave && t >= 2) {
-                // chunk t-2, finished in iteration t-1: whole 128-byte row pieces per lane group,
-                // lane -> (row l/8 of eight rows, 16 bytes l%8).  Nontemporal: the output is written
-                // once and must not displace Q and K, which the sibling slices re-read, from L2.
-                const int c = t - 2;
-                const int cshift = (c == n - 1) ? last_shift : 0;
-                const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * D + c0;  // + row * D
-                if (!kOut16) {
-                    float* oc = og + tile_off + 4 * (l & 7);
-                    const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
-#pragma unroll
-                    for (int m = 0; m < 8; ++m) {
-                        const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
-                        const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                        if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
-                    }
-                } else {
-                    // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
-                    uint16_t* oc = og16 + tile_off + 8 * (l & 3);
-                    const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 2) * 36 + 8 * (l & 3)];
-#pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        const int row = 16 * m + (l >> 2);  // row block m / 2
-                        const float* src = ot + (m >> 1) * (32 * 36) + (16 * (m & 1)) * 36;
-                        const f32x4 a = *reinterpret_cast<const f32x4*>(src);
-                        const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
-                        const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
-                        if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * D));
-                    }
-                }
-            }
-            if (state_wave && t < n) {
-                // G4: S = gamma^L S + K^T (Gam V) for the tile this wave owns; publish S^T(t+1)
-                const float gl = shift ? sm.pw[kChunk - shift] : gl_full;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) S[r] *= gl;
-                const uint16_t* k_tr = &sm.k[qb][tr_off_k];
-                const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
-#pragma unroll
-                for (int f = 0; f < 4; ++f)
-                    S = mfma32(frag_tr(k_tr + f * RSQ, 32 * RSQ), frag_tr(vs_tr + f * RSVS, 32 * RSVS), S);
-                if (kOut) publish_state((t + 1) & 1);
+            for (int f = 0; f < 4; ++f) {
+                ak[f] = frag_tr(k_tr + f * RSQ, 32 * RSQ);
+                bv[f] = frag_tr(vs_tr + f * RSVS, 32 * RSVS);
             }
         }
-        __syncthreads();  // chunk t+1 tiles, P(t), S^T(t+1) visible; everything read in this iteration is free
+        f32x16 acc = zero16();
+        if (kG1) {
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) acc = mfma32(kf[s], qf[s], acc);
+        }
+        if (kG4) {
+            // S = gamma^L S + K^T (Gam V) for the tile this wave owns
+            const float gl = shift ? sm.pw[kChunk - shift] : gl_full;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[r] *= gl;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) S = mfma32(ak[f], bv[f], S);
+        }
+        if (kG1) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
+            sm.pfrag[qb][w][0][l] = pack_half<E>(acc, 0);
+            sm.pfrag[qb][w][1][l] = pack_half<E>(acc, 1);
+        }
+        if (kG4 && kOut) publish_state((t + 1) & 1);  // S^T(t+1) for the G3 waves
+    };
+
+    // Output waves, row block it_own.  kG2: finish chunk t-1 (O^T += V^T P^T over the score tiles of
+    // the row block) and hand it to the store wave; kG3: start chunk t (O^T = S^T Q^T, rows scaled
+    // by gamma^(i+1)).
+    f32x16 o = zero16();  // the row block of the chunk in progress
+    auto output = [&](int t, auto do_g2, auto do_g3, auto do_g4) {
+        constexpr bool kG2 = decltype(do_g2)::value, kG3 = decltype(do_g3)::value, kG4 = decltype(do_g4)::value;
+        const int qb = t & 1;
+        u32x4 sf[D / 16], qf[D / 16], vt[4], pf[4], ak[4], bv[4];
+        if (kG3) {
+            const uint16_t* st_rd = &sm.st[qb][st_rd_off];
+            const uint16_t* qa = &sm.q[qb][row_off + 32 * it_own * RSQ];
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) { sf[s] = frag16(st_rd + 16 * s); qf[s] = frag16(qa + 16 * s); }
+        }
+        if (kG2) {
+            const int pb = (t - 1) & 1;
+            const uint16_t* v_tr = &sm.v[(t - 1) % 3][tr_off_v];
+            if (it_own == 0) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) { vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV); pf[hh] = sm.pfrag[pb][0][hh][l]; }
+            } else {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV);
+                    pf[hh] = sm.pfrag[pb][2][hh][l];
+                    vt[2 + hh] = frag_tr(v_tr + 16 * (2 + hh) * RSV, 8 * RSV);
+                    pf[2 + hh] = sm.pfrag[pb][1][hh][l];
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) o = mfma32(vt[hh], pf[hh], o);
+            if (it_own != 0) {
+#pragma unroll
+                for (int hh = 2; hh < 4; ++hh) o = mfma32(vt[hh], pf[hh], o);
+            }
+        }
+        if (kG4) {
+            const uint16_t* k_tr = &sm.k[qb][tr_off_k];
+            const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                ak[f] = frag_tr(k_tr + f * RSQ, 32 * RSQ);
+                bv[f] = frag_tr(vs_tr + f * RSVS, 32 * RSVS);
+            }
+        }
+        f32x16 o_next = zero16();
+        if (kG3) {
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) o_next = mfma32(sf[s], qf[s], o_next);
+        }
+        if (kG4) {
+            const int shift4 = (t == n - 1) ? last_shift : 0;
+            const float gl = shift4 ? sm.pw[kChunk - shift4] : gl_full;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[r] *= gl;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) S = mfma32(ak[f], bv[f], S);
+            publish_state((t + 1) & 1);
+        }
+        if (kG2) {
+            // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
+            float* ot = &sm.obuf[qb][it_own][ln * 36 + 4 * g];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
+                *reinterpret_cast<f32x4*>(ot + 8 * qd) = val;
+            }
+        }
+        if (kG3) {
+            const int shift = (t == n - 1) ? last_shift : 0;
+            const float lam = shift ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[r] = o_next[r] * lam;
+        }
+    };
+
+    // Store wave: chunk t-2, finished in iteration t-1: whole row pieces per lane group.
+    // Nontemporal: the output is written once and must not displace Q and K, which the sibling
+    // slices re-read, from L2.
+    auto store_chunk = [&](int t) {
+        const int c = t - 2;
+        const int cshift = (c == n - 1) ? last_shift : 0;
+        const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * D + c0;  // + row * D
+        if (!kOut16) {
+            // 128-byte row pieces: lane -> (row l/8 of eight rows, 16 bytes l%8)
+            float* oc = og + tile_off + 4 * (l & 7);
+            const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
+                const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
+            }
+        } else {
+            // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
+            uint16_t* oc = og16 + tile_off + 8 * (l & 3);
+            const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 2) * 36 + 8 * (l & 3)];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int row = 16 * m + (l >> 2);  // row block m / 2
+                const float* src = ot + (m >> 1) * (32 * 36) + (16 * (m & 1)) * 36;
+                const f32x4 a = *reinterpret_cast<const f32x4*>(src);
+                const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
+                const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * D));
+            }
+        }
     };
 
     // The loaders and the compute waves run separate loops (so that the register stages are live
@@ -449,8 +511,45 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             }
         for (; t <= t_end; ++t) __syncthreads();  // iterations that load nothing
     } else {
+        const std::true_type yes;
+        const std::false_type no;
         __syncthreads();
-        for (int t = 0; t <= t_end; ++t) iteration(t);
+        // every branch below executes one barrier per iteration t = 0 .. t_end
+        if (score_wave) {
+            for (int t = 0; t <= t_end; ++t) {
+                if (t < n) {
+                    if (state_wave) score_state(t, yes, yes);
+                    else score_state(t, yes, no);
+                }
+                __syncthreads();  // chunk t+1 tiles, P(t), S^T(t+1) visible; everything read in this iteration is free
+            }
+        } else if (out_wave) {
+            if (state_wave) {
+                output(0, no, yes, yes);
+                __syncthreads();
+                for (int t = 1; t < n; ++t) {
+                    output(t, yes, yes, yes);
+                    __syncthreads();
+                }
+            } else {
+                output(0, no, yes, no);
+                __syncthreads();
+                for (int t = 1; t < n; ++t) {
+                    output(t, yes, yes, no);
+                    __syncthreads();
+                }
+            }
+            output(n, yes, no, no);
+            __syncthreads();
+            __syncthreads();  // iteration n + 1: the store wave's last chunk
+        } else {
+            // wave 5 (state tile 3 where it exists, and the stores), and in the pre-pass every state wave
+            for (int t = 0; t <= t_end; ++t) {
+                if (state_wave && t < n) score_state(t, no, yes);
+                if (store_wave && t >= 2) store_chunk(t);
+                __syncthreads();
+            }
+        }
     }
 
     // ---- hand the state on

@@ -70,8 +70,8 @@ int wide_pre_split(long BH, int nseg, int seg_chunks) {
 // count) pair.  Each kernel is priced as the smooth maximum (x^p + y^p)^(1/p) of its dependent
 // chain (rounds of resident workgroups x chunks per segment x the per-chunk time of a lone
 // workgroup) and of its HBM/last-level-cache transfer time; a call is the sum of its kernels plus
-// a fixed cost per call.  The constants are a least-squares fit (6 % rms) to event-timed runs of
-// both kernels at 1 to 64 segments over B*H in 1..256 and N in 256..65536; the tabulated runs are
+// a fixed cost per call.  The constants are a least-squares fit (5 % rms) to event-timed runs of
+// both kernels at 1 to 64 segments over B*H in 1..768 and N in 256..65536; the tabulated runs are
 // kept with the profiles, and a host test checks the planner's picks against them.
 struct CostModel {
     double wide_chunk_us, wide_pre_chunk_us;    // lone wide workgroup: walk and pre-pass per chunk
@@ -84,10 +84,10 @@ struct CostModel {
     double wide_crowded;                        // transfer-time factor with more wide workgroups than CUs
     int wide_slots;                             // wide workgroups resident on the device
 };
-constexpr CostModel kCost128 = {2.524, 0.801, 0.871, 0.373, 8.0e6, 6.470e6, 6.357e6, 5.550e6,
-                                5.27, 11.63, 0.348, 2.131, 2.0, 1.217, 512};
-constexpr CostModel kCost64 = {1.812, 0.452, 0.614, 0.303, 7.621e6, 6.056e6, 8.0e6, 5.809e6,
-                               4.41, 10.60, 0.345, 2.419, 2.286, 1.131, 1024};
+constexpr CostModel kCost128 = {2.726, 1.020, 0.896, 0.361, 8.0e6, 6.746e6, 8.0e6, 5.816e6,
+                                3.62, 10.07, 0.353, 2.287, 2.0, 1.260, 512};
+constexpr CostModel kCost64 = {1.951, 0.574, 0.632, 0.277, 7.315e6, 5.988e6, 8.0e6, 5.662e6,
+                               3.53, 9.65, 0.345, 2.885, 2.617, 1.126, 1024};
 constexpr double kOneKernelFloorUs = 11.0;    // shortest call seen end to end, one and three kernels
 constexpr double kThreeKernelFloorUs = 17.0;
 constexpr int kCoopSlots = 256;               // one column-split workgroup per compute unit
@@ -107,7 +107,8 @@ double predicted_us(bool coop, long BH, int N, int D, bool out16, int nseg, int 
         const long per_seg = BH * (D / 32);
         const double bw = m.coop_bw_cached * (1.0 - spill) + m.coop_bw_streamed * spill;
         const long rounds = (per_seg * nseg + kCoopSlots - 1) / kCoopSlots;
-        const double walk = smooth_max(rounds * seg_chunks * m.coop_chunk_us, (in_bytes + out_bytes) / bw, m.coop_p);
+        // the walk's software pipeline runs two iterations beyond the chunks of a segment
+        const double walk = smooth_max(rounds * (seg_chunks + 2) * m.coop_chunk_us, (in_bytes + out_bytes) / bw, m.coop_p);
         if (nseg == 1) return fmax(kOneKernelFloorUs, m.one_kernel_us + walk);
         const long pre_rounds = (per_seg * (nseg - 1) + kCoopSlots - 1) / kCoopSlots;
         const double pre = smooth_max(pre_rounds * seg_chunks * m.coop_pre_chunk_us, pre_bytes / bw, m.coop_p);

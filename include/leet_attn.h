@@ -244,9 +244,9 @@ int leet_attn_release_workspace(void);
  * Tuning knob: which kernel a bf16 or fp16 prefill uses.  Both compute the same chunked form (Alg. 2
  * with the decaying mask) and pass the same parity tests; they differ in how the work is split.
  *   LEET_KERNEL_WIDE          one workgroup per (sequence, segment), all d value columns
- *   LEET_KERNEL_COLUMN_SPLIT  d/32 workgroups per (sequence, segment), 32 value columns each,
+ *   LEET_KERNEL_COLUMN_SPLIT  dv/32 workgroups per (sequence, segment), 32 value columns each,
  *                             placed on one XCD; fewer segments needed to fill the device
- *                             (16-bit inputs, square shapes; other forms run wide)
+ *                             (16-bit inputs, every supported shape; fp32 runs wide)
  *   LEET_KERNEL_AUTO          (default) the library prices both kernels at each candidate segment
  *                             count with a cost model fitted to measurements and takes the
  *                             cheapest pair; leet_attn_query_plan reports the outcome
@@ -279,6 +279,8 @@ int leet_attn_get_decode_store(void);
  * pointer may be NULL.  Host-only; touches no device.
  */
 int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int *nseg, int *kernel);
+/* The same for rank r and value width dv given separately (shapes as for leet_attn_forward_rd). */
+int leet_attn_query_plan_rd(int B, int H, int N, int r, int dv, int dtype, int segments, int *nseg, int *kernel);
 
 /* Static, never-NULL description of a leet_status value. */
 const char *leet_attn_strerror(int status);

@@ -39,6 +39,7 @@ EXPORTED_SYMBOLS = (
     "leet_attn_set_bf16_kernel",
     "leet_attn_get_bf16_kernel",
     "leet_attn_query_plan",
+    "leet_attn_query_plan_rd",
     "leet_attn_set_decode_store",
     "leet_attn_get_decode_store",
     "leet_attn_workspace_bytes",
@@ -100,6 +101,8 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_get_bf16_kernel.restype = i
     lib.leet_attn_query_plan.argtypes = [i, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
     lib.leet_attn_query_plan.restype = i
+    lib.leet_attn_query_plan_rd.argtypes = [i, i, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.leet_attn_query_plan_rd.restype = i
     lib.leet_attn_set_decode_store.argtypes = [i]
     lib.leet_attn_set_decode_store.restype = i
     lib.leet_attn_get_decode_store.argtypes = []
@@ -188,6 +191,15 @@ def query_plan(B: int, H: int, N: int, d: int, dtype: int, segments: int = 0):
     st = lib.leet_attn_query_plan(B, H, N, d, dtype, segments, ctypes.byref(nseg), ctypes.byref(kern))
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_query_plan")
+    return nseg.value, kern.value
+
+
+def query_plan_rd(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments: int = 0):
+    """``query_plan`` for rank r and value width dv given separately."""
+    nseg, kern = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib.leet_attn_query_plan_rd(B, H, N, r, dv, dtype, segments, ctypes.byref(nseg), ctypes.byref(kern))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_query_plan_rd")
     return nseg.value, kern.value
 
 

@@ -12,8 +12,8 @@
 namespace leet {
 hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
 hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
-hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream);
-hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream);
+hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
+hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
@@ -33,7 +33,7 @@ namespace {
 
 using leet::kChunk;
 
-// fp32 and the rank-128, width-256 shape: sequences are cut into segments so that about this many
+// fp32: sequences are cut into segments so that about this many
 // workgroups exist (one per compute unit of a 256-CU device measured best), but no segment is
 // shorter than a minimum number of chunks: each extra segment costs one D x DV fp32 state written,
 // scanned and re-read, and every segment but the last has its K and V read twice.  The fp32
@@ -66,12 +66,12 @@ int wide_pre_split(long BH, int nseg, int seg_chunks) {
     return (nseg > 1 && seg_chunks >= 16 && seg_chunks % 2 == 0 && BH * (nseg - 1) <= 256) ? 2 : 1;
 }
 
-// Cost model of the 16-bit square shapes (d = 64, 128), in microseconds, for one (kernel, segment
+// Cost model of the 16-bit shapes, in microseconds, for one (kernel, segment
 // count) pair.  Each kernel is priced as the smooth maximum (x^p + y^p)^(1/p) of its dependent
 // chain (rounds of resident workgroups x chunks per segment x the per-chunk time of a lone
 // workgroup) and of its HBM/last-level-cache transfer time; a call is the sum of its kernels plus
 // a fixed cost per call.  The constants are a least-squares fit (5 % rms) to event-timed runs of
-// both kernels at 1 to 64 segments over B*H in 1..768 and N in 256..65536; the tabulated runs are
+// both kernels at 1 to 64 segments over B*H in 1..768 and N in 256..65536 (each of the three shapes); the tabulated runs are
 // kept with the profiles, and a host test checks the planner's picks against them.
 struct CostModel {
     double wide_chunk_us, wide_pre_chunk_us;    // lone wide workgroup: walk and pre-pass per chunk
@@ -88,6 +88,9 @@ constexpr CostModel kCost128 = {2.726, 1.020, 0.896, 0.361, 8.0e6, 6.746e6, 8.0e
                                 3.62, 10.07, 0.353, 2.287, 2.0, 1.260, 512};
 constexpr CostModel kCost64 = {1.951, 0.574, 0.632, 0.277, 7.315e6, 5.988e6, 8.0e6, 5.662e6,
                                3.53, 9.65, 0.345, 2.885, 2.617, 1.126, 1024};
+// rank 128, value width 256: one wide workgroup per compute unit (512 threads)
+constexpr CostModel kCost128x256 = {3.402, 1.695, 0.827, 0.412, 8.0e6, 6.681e6, 6.391e6, 4.646e6,
+                                    4.22, 10.35, 0.426, 2.532, 2.0, 1.163, 256};
 constexpr double kOneKernelFloorUs = 11.0;    // shortest call seen end to end, one and three kernels
 constexpr double kThreeKernelFloorUs = 17.0;
 constexpr int kCoopSlots = 256;               // one column-split workgroup per compute unit
@@ -95,16 +98,16 @@ constexpr int kCoopSlots = 256;               // one column-split workgroup per 
 double smooth_max(double a, double b, double p) { return pow(pow(a, p) + pow(b, p), 1.0 / p); }
 
 // nseg is a segment count that make_plan has already rounded (nseg = ceil(nchunks / seg_chunks))
-double predicted_us(bool coop, long BH, int N, int D, bool out16, int nseg, int seg_chunks) {
-    const CostModel& m = D == 128 ? kCost128 : kCost64;
-    const double in_bytes = (double)BH * N * D * 6, out_bytes = (double)BH * N * D * (out16 ? 2 : 4);
+double predicted_us(bool coop, long BH, int N, int D, int DV, bool out16, int nseg, int seg_chunks) {
+    const CostModel& m = D == 64 ? kCost64 : DV == 128 ? kCost128 : kCost128x256;
+    const double in_bytes = (double)BH * N * (2 * D + DV) * 2, out_bytes = (double)BH * N * DV * (out16 ? 2 : 4);
     // share of the inputs that no longer stays in the last-level cache: none up to 0.6 of its size
     // (the outputs pass through it too), all from 1.2
     const double spill = fmin(1.0, fmax(0.0, (in_bytes / (double)kLastLevelCacheBytes - 0.6) / 0.6));
-    const double pre_bytes = (double)BH * N * D * 4 * (nseg - 1) / nseg;  // K and V of all segments but the last
-    double scan = nseg > 1 ? nseg * fmax(m.scan_state_us, (double)BH * D * D * 8 / 5e6) : 0.0;
+    const double pre_bytes = (double)BH * N * (D + DV) * 2 * (nseg - 1) / nseg;  // K and V of all segments but the last
+    double scan = nseg > 1 ? nseg * fmax(m.scan_state_us, (double)BH * D * DV * 8 / 5e6) : 0.0;
     if (coop) {
-        const long per_seg = BH * (D / 32);
+        const long per_seg = BH * (DV / 32);
         const double bw = m.coop_bw_cached * (1.0 - spill) + m.coop_bw_streamed * spill;
         const long rounds = (per_seg * nseg + kCoopSlots - 1) / kCoopSlots;
         // the walk's software pipeline runs two iterations beyond the chunks of a segment
@@ -129,16 +132,16 @@ double predicted_us(bool coop, long BH, int N, int D, bool out16, int nseg, int 
 // out16: the output is written in the (16-bit) input type
 // D: width of q and k rows (rank); DV: width of v and out rows
 //
-// 16-bit square shapes: every eligible (kernel, segment count) pair is priced with the cost model
+// 16-bit inputs: every eligible (kernel, segment count) pair is priced with the cost model
 // and the cheapest taken (ties go to fewer segments, then to the column-split kernel).  A caller's
-// segment count or kernel choice narrows the candidates.  Other shapes and fp32 keep the rule of
+// segment count or kernel choice narrows the candidates.  fp32 keeps the rule of
 // about one workgroup per compute unit with a minimum segment length.
 bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
     const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
-    const bool coop_able = dtype != LEET_F32 && D == DV;  // the column-split kernel: 16-bit inputs, square shapes
+    const bool coop_able = dtype != LEET_F32;  // the column-split kernel: 16-bit inputs, every supported shape
     auto finish = [&](bool coop, int nseg, int seg_chunks) {
-        const long per_seg = coop ? BH * (D / 32) : BH;  // workgroups one segment of every sequence gives
+        const long per_seg = coop ? BH * (DV / 32) : BH;  // workgroups one segment of every sequence gives
         if (per_seg * (long)nseg >= (1L << 28)) return false;
         plan->coop = coop;
         plan->nseg = nseg;
@@ -154,7 +157,7 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segment
         *nseg = (nchunks + *seg_chunks - 1) / *seg_chunks;
     };
 
-    if (dtype != LEET_F32 && D == DV) {
+    if (dtype != LEET_F32) {
         // the column-split kernel needs four chunks to fill its pipeline and is not offered below
         const bool try_coop = coop_able && choice != LEET_KERNEL_WIDE && (nchunks >= 4 || choice == LEET_KERNEL_COLUMN_SPLIT);
         const bool try_wide = !(coop_able && choice == LEET_KERNEL_COLUMN_SPLIT);
@@ -169,7 +172,7 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segment
             if (segments == 0 && nseg > 1 && seg_chunks < 2) break;
             for (int c = 1; c >= 0; --c) {
                 if (c ? !try_coop : !try_wide) continue;
-                const double t = predicted_us(c != 0, BH, N, D, out16, nseg, seg_chunks);
+                const double t = predicted_us(c != 0, BH, N, D, DV, out16, nseg, seg_chunks);
                 if (!have || t < best * 0.98) {
                     have = true; best = t; best_coop = c != 0; best_nseg = nseg; best_chunks = seg_chunks;
                 }
@@ -302,7 +305,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
 
     const bool coop = plan.coop;
     auto launch_states = [&]() {
-        return coop   ? leet::launch_fwd_16bit_coop_states(p, (int)BH, d, f16, s)
+        return coop   ? leet::launch_fwd_16bit_coop_states(p, (int)BH, d, dv, f16, s)
                : in16 ? leet::launch_fwd_16bit_states(pre, (int)BH, d, dv, f16, s)
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
@@ -310,7 +313,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
         return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk, p.state_step, d, dv, s);
     };
     auto launch_walk = [&]() {
-        return coop   ? leet::launch_fwd_16bit_coop_walk(p, (int)BH, d, f16, out16, s)
+        return coop   ? leet::launch_fwd_16bit_coop_walk(p, (int)BH, d, dv, f16, out16, s)
                : in16 ? leet::launch_fwd_16bit_walk(p, (int)BH, d, dv, f16, out16, s)
                       : leet::launch_fwd_f32_walk(p, (int)BH, d, s);
     };
@@ -457,15 +460,19 @@ int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, con
                                           stream);
 }
 
-int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int* nseg, int* kernel) {
+int leet_attn_query_plan_rd(int B, int H, int N, int r, int dv, int dtype, int segments, int* nseg, int* kernel) {
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
-    if (!shape_ok(d, dtype, &status)) return status;
+    if (!shape_ok(r, dv, dtype, &status)) return status;
     Plan plan;
-    if (!make_plan((long)B * H, N, d, d, dtype, false, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan((long)B * H, N, r, dv, dtype, false, segments, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;
     if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
     return LEET_OK;
+}
+
+int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int* nseg, int* kernel) {
+    return leet_attn_query_plan_rd(B, H, N, d, d, dtype, segments, nseg, kernel);
 }
 
 int leet_attn_decode_step_rd(const void* q, const void* k, const void* v, const float* gamma,

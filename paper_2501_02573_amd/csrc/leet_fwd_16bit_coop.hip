@@ -9,7 +9,7 @@
 //
 // but a different split of the work, made for few, long sequences.  Value columns are
 // independent of one another (O[:, c] and S[:, c] need only V[:, c]), so a sequence is
-// handled by D/32 workgroups, one per 32-column slice, on D/32 compute units; each reads
+// handled by DV/32 workgroups, one per 32-column slice, on DV/32 compute units; each reads
 // all of Q and K (the copies of one sequence are placed on one XCD so that all but one of
 // the reads hit its L2) and its own 32 columns of V, and writes its 32 columns of O.
 //
@@ -136,7 +136,8 @@ constexpr int kCoopLoaderWaves = LEET_COOP_LW;
 constexpr int kCoopStages = LEET_COOP_NS;
 constexpr int kCoopThreads = 384 + 64 * kCoopLoaderWaves;
 
-template <int D, bool kOut, typename E, bool kOut16>
+// D: width of q and k rows (rank); DV: width of v and out rows (DV / 32 slices per sequence).
+template <int D, int DV, bool kOut, typename E, bool kOut16>
 __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams p, int ngroups, int map_mode) {
     using namespace coop;
     auto mfma32 = [](u32x4 a, u32x4 b, f32x16 c) { return E::mfma32(a, b, c); };
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     constexpr int NS = kCoopStages;             // register stages of the loaders
     constexpr int VPL = kChunk * 4 / NL;        // V pieces per loader thread per chunk
     constexpr int VRS = NL / 4;                 // rows between two V pieces of one loader thread
-    constexpr int SL = D / 32;     // column slices (workgroups) per sequence segment
+    constexpr int SL = DV / 32;    // column slices (workgroups) per sequence segment
     constexpr int DT = D / 32;     // 32-row state tiles of the slice
     constexpr int PR = D / 8;      // 16-byte pieces per Q/K row
     constexpr int QPL = kChunk * PR / NL;  // Q (and K) pieces per loader thread per chunk
@@ -185,12 +186,12 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     const int n = (tok_end - tok_begin + kChunk - 1) / kChunk;   // chunks of this segment
     const int last_shift = n * kChunk - (tok_end - tok_begin);   // empty rows at the top of the last chunk's tile
 
-    const size_t seq_off = (size_t)bh * p.N * D;
+    const size_t seq_off = (size_t)bh * p.N * D, seq_off_v = (size_t)bh * p.N * DV;
     const uint16_t* qg = reinterpret_cast<const uint16_t*>(p.q) + seq_off;
     const uint16_t* kg = reinterpret_cast<const uint16_t*>(p.k) + seq_off;
-    const uint16_t* vg = reinterpret_cast<const uint16_t*>(p.v) + seq_off;
-    float* og = static_cast<float*>(p.out) + seq_off;                       // fp32 output
-    uint16_t* og16 = static_cast<uint16_t*>(p.out) + seq_off;               // output in the input type
+    const uint16_t* vg = reinterpret_cast<const uint16_t*>(p.v) + seq_off_v;
+    float* og = static_cast<float*>(p.out) + seq_off_v;                     // fp32 output
+    uint16_t* og16 = static_cast<uint16_t*>(p.out) + seq_off_v;             // output in the input type
 
     {
         const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
@@ -206,12 +207,12 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     if (state_wave) {
         const float* src = nullptr;
         if (kOut) {
-            if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
-            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * D;
+            if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * DV : nullptr;
+            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * DV;
         }
         if (src) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] = src[dk_of(r) * D + c0 + ln];
+            for (int r = 0; r < 16; ++r) S[r] = src[dk_of(r) * DV + c0 + ln];
         }
     }
     // S^T[c][dk] in LDS: registers 8h..8h+7 are dk = 32 t + 16 h + 8 g + (0..7)
@@ -242,10 +243,10 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     auto prefetch = [&](Stage& st, int c) {
         c = min(c, n - 1);
         const int shift = (c == n - 1) ? last_shift : 0;
-        const size_t base = (size_t)(tok_begin + c * kChunk - shift) * D;  // wave-uniform
-        const uint16_t* qc = qg + base;
-        const uint16_t* kc = kg + base;
-        const uint16_t* vc = vg + base;
+        const size_t tok0 = (size_t)(tok_begin + c * kChunk - shift);  // wave-uniform
+        const uint16_t* qc = qg + tok0 * D;
+        const uint16_t* kc = kg + tok0 * D;
+        const uint16_t* vc = vg + tok0 * DV;
 #pragma unroll
         for (int m = 0; m < QPL; ++m) {
             const int row = max(qk_row + m * RPL, shift);
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         }
 #pragma unroll
         for (int m = 0; m < VPL; ++m)
-            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m, shift) * D + c0 + v_cc * 8));
+            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m, shift) * DV + c0 + v_cc * 8));
     };
 
     __syncthreads();  // tables, S^T(0) visible
@@ -449,7 +450,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     auto store_chunk = [&](int t) {
         const int c = t - 2;
         const int cshift = (c == n - 1) ? last_shift : 0;
-        const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * D + c0;  // + row * D
+        const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * DV + c0;  // + row * DV
         if (!kOut16) {
             // 128-byte row pieces: lane -> (row l/8 of eight rows, 16 bytes l%8)
             float* oc = og + tile_off + 4 * (l & 7);
@@ -458,7 +459,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             for (int m = 0; m < 8; ++m) {
                 const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
                 const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * D));
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * DV));
             }
         } else {
             // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
@@ -471,7 +472,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
                 const f32x4 a = *reinterpret_cast<const f32x4*>(src);
                 const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
                 const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * D));
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * DV));
             }
         }
     };
@@ -555,13 +556,13 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // ---- hand the state on
     float* dst = nullptr;
     if (kOut) {
-        if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * D;
+        if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * DV;
     } else {
-        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * D;
+        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * DV;
     }
     if (dst && state_wave) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dst[dk_of(r) * D + c0 + ln] = S[r];
+        for (int r = 0; r < 16; ++r) dst[dk_of(r) * DV + c0 + ln] = S[r];
     }
 }
 
@@ -570,31 +571,33 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
 bool g_coop_consecutive_ids = false;
 
 namespace {
-template <int D, bool kOut, typename E, bool kOut16>
+template <int D, int DV, bool kOut, typename E, bool kOut16>
 hipError_t launch_coop(const FwdParams& p, int BH, hipStream_t stream) {
     const int ngroups = BH * (kOut ? p.nseg : p.nseg - 1);
     if (ngroups <= 0) return hipSuccess;
-    const int blocks = 8 * (D / 32) * ((ngroups + 7) / 8);
+    const int blocks = 8 * (DV / 32) * ((ngroups + 7) / 8);
     const int map_mode = g_coop_consecutive_ids ? 1 : 0;
-    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, kOut, E, kOut16>), dim3(blocks), dim3(kCoopThreads), 0, stream, p, ngroups, map_mode);
+    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, DV, kOut, E, kOut16>), dim3(blocks), dim3(kCoopThreads), 0, stream, p, ngroups, map_mode);
     return hipGetLastError();
 }
 
 template <bool kOut, typename E, bool kOut16>
-hipError_t launch_coop_d(const FwdParams& p, int BH, int D, hipStream_t stream) {
-    return D == 64 ? launch_coop<64, kOut, E, kOut16>(p, BH, stream) : launch_coop<128, kOut, E, kOut16>(p, BH, stream);
+hipError_t launch_coop_d(const FwdParams& p, int BH, int D, int DV, hipStream_t stream) {
+    if (D == 64) return launch_coop<64, 64, kOut, E, kOut16>(p, BH, stream);
+    if (DV == 128) return launch_coop<128, 128, kOut, E, kOut16>(p, BH, stream);
+    return launch_coop<128, 256, kOut, E, kOut16>(p, BH, stream);
 }
 }  // namespace
 
-// D = 64 or 128 (square shapes); f16: fp16 instead of bf16 inputs; out16: output in the input type
-hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, bool f16, hipStream_t stream) {
+// (D, DV) one of (64, 64), (128, 128), (128, 256); f16: fp16 instead of bf16 inputs; out16: output in the input type
+hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream) {
     if (p.nseg <= 1) return hipSuccess;
-    return f16 ? launch_coop_d<false, ElemF16, false>(p, BH, D, stream) : launch_coop_d<false, ElemBf16, false>(p, BH, D, stream);
+    return f16 ? launch_coop_d<false, ElemF16, false>(p, BH, D, DV, stream) : launch_coop_d<false, ElemBf16, false>(p, BH, D, DV, stream);
 }
 
-hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, bool f16, bool out16, hipStream_t stream) {
-    if (f16) return out16 ? launch_coop_d<true, ElemF16, true>(p, BH, D, stream) : launch_coop_d<true, ElemF16, false>(p, BH, D, stream);
-    return out16 ? launch_coop_d<true, ElemBf16, true>(p, BH, D, stream) : launch_coop_d<true, ElemBf16, false>(p, BH, D, stream);
+hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream) {
+    if (f16) return out16 ? launch_coop_d<true, ElemF16, true>(p, BH, D, DV, stream) : launch_coop_d<true, ElemF16, false>(p, BH, D, DV, stream);
+    return out16 ? launch_coop_d<true, ElemBf16, true>(p, BH, D, DV, stream) : launch_coop_d<true, ElemBf16, false>(p, BH, D, DV, stream);
 }
 
 }  // namespace leet

@@ -319,11 +319,18 @@ RD_SHAPES = [
 ]
 
 
+@pytest.fixture(params=["auto", "wide", "column-split"])
+def kernel_choice(request, B):
+    B.set_bf16_kernel({"auto": B.KERNEL_AUTO, "wide": B.KERNEL_WIDE, "column-split": B.KERNEL_COLUMN_SPLIT}[request.param])
+    yield request.param
+    B.set_bf16_kernel(B.KERNEL_AUTO)
+
+
 @pytest.mark.parametrize("shape", RD_SHAPES, ids=lambda s: "B%d_H%d_N%d_%s_out16%d_seg%d" % s)
-def test_rank_128_value_width_256(B, shape):
+def test_rank_128_value_width_256(B, shape, kernel_choice):
     Bn, H, N, dtype, out16, segs = shape
     r, dv = 128, 256
-    say(f"case r={r} dv={dv} shape={shape}")
+    say(f"case r={r} dv={dv} shape={shape} kernel={kernel_choice}")
     gamma = torch.tensor(([0.0, 1.0, 0.5, 0.999, 0.9] * 2)[:H], dtype=torch.float32)
     q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N + 1, r, dv, dtype, seed=5000 + N, gamma=gamma)
     rng = np.random.default_rng(N)

@@ -189,7 +189,7 @@ def main():
     cfg = W.CONFIG3
     nseg3, kern3 = binding.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, binding.LEET_BF16, args.segments)
     kernel_ran = "column-split" if kern3 == binding.KERNEL_COLUMN_SPLIT else "wide"
-    walk_name = {"wide": "fwd_16bit_kernel<128,128,true,bf16>", "column-split": "fwd_16bit_coop_kernel<128,true,bf16>"}[kernel_ran]
+    walk_name = {"wide": "fwd_16bit_kernel<128,128,true,bf16>", "column-split": "fwd_16bit_coop_kernel<128,128,true,bf16>"}[kernel_ran]
     ms_eager, ms_graph, kms, ms_events = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup,
                                                      args.segments, not args.no_graph)
     ms = ms_eager

@@ -138,7 +138,7 @@ constexpr int kCoopThreads = 384 + 64 * kCoopLoaderWaves;
 
 // D: width of q and k rows (rank); DV: width of v and out rows (DV / 32 slices per sequence).
 template <int D, int DV, bool kOut, typename E, bool kOut16>
-__global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams p, int ngroups, int map_mode) {
+__global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams p, int ngroups) {
     using namespace coop;
     auto mfma32 = [](u32x4 a, u32x4 b, f32x16 c) { return E::mfma32(a, b, c); };
     constexpr int NT = kCoopThreads;            // six compute waves and the loader waves
@@ -156,10 +156,10 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
 
     // Block -> (sequence segment, column slice).  Consecutive block ids go round-robin over
     // the 8 XCDs; the SL slices of one segment take ids that are equal modulo 8, so they share
-    // one L2 (map_mode 1 numbers them consecutively instead; measurement only).
+    // one L2 (measured on config 3 with FETCH_SIZE: 201.5 MB fetched per launch, the compulsory
+    // Q + K + V, against 671 MB with the slices numbered consecutively).
     const int gx = blockIdx.x & 7, rest = blockIdx.x >> 3;
-    int slice = rest % SL, group = (rest / SL) * 8 + gx;
-    if (map_mode == 1) { slice = blockIdx.x % SL; group = blockIdx.x / SL; }
+    const int slice = rest % SL, group = (rest / SL) * 8 + gx;
     if (group >= ngroups) return;
     const int nseg_launch = kOut ? p.nseg : p.nseg - 1;
     const int bh = group / nseg_launch, seg = group % nseg_launch;
@@ -566,18 +566,13 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     }
 }
 
-// Measurement switch: number the slices of a segment consecutively (spreading them over the
-// XCDs) instead of placing them on one XCD.  Off by default.
-bool g_coop_consecutive_ids = false;
-
 namespace {
 template <int D, int DV, bool kOut, typename E, bool kOut16>
 hipError_t launch_coop(const FwdParams& p, int BH, hipStream_t stream) {
     const int ngroups = BH * (kOut ? p.nseg : p.nseg - 1);
     if (ngroups <= 0) return hipSuccess;
     const int blocks = 8 * (DV / 32) * ((ngroups + 7) / 8);
-    const int map_mode = g_coop_consecutive_ids ? 1 : 0;
-    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, DV, kOut, E, kOut16>), dim3(blocks), dim3(kCoopThreads), 0, stream, p, ngroups, map_mode);
+    hipLaunchKernelGGL((fwd_16bit_coop_kernel<D, DV, kOut, E, kOut16>), dim3(blocks), dim3(kCoopThreads), 0, stream, p, ngroups);
     return hipGetLastError();
 }
 

@@ -39,7 +39,6 @@ using leet::kChunk;
 // scanned and re-read, and every segment but the last has its K and V read twice.  The fp32
 // kernel is bound by MFMA latency per chunk, not by HBM, so it takes much shorter segments.
 constexpr int kTargetWorkgroups = 256;
-constexpr int kMinSegChunks16 = 8;
 constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;  // MI355X Infinity Cache
@@ -182,12 +181,13 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segment
         return finish(best_coop, best_nseg, best_chunks);
     }
 
+    // fp32
     long want;
     if (segments > 0) {
         want = segments;
     } else {
         want = (kTargetWorkgroups + BH - 1) / BH;
-        long cap = nchunks / (dtype == LEET_F32 ? kMinSegChunksF32 : kMinSegChunks16);
+        long cap = nchunks / kMinSegChunksF32;
         if (cap < 1) cap = 1;
         if (want > cap) want = cap;
     }

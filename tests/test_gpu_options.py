@@ -448,3 +448,37 @@ def test_random_legal_shapes_and_options(B, case):
                                   state_in=None if s_in is None else W.to_f64(s_in))
     check(to_np(out), ref, TOL[dtype], "out")
     check(to_np(S), s_ref, TOL[dtype], "final state")
+
+
+def _random_planned_cases(n, seed=4242):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = ["bf16", "f16"][int(rng.integers(0, 2))]
+        d = int(rng.choice([64, 128]))
+        dv = 256 if (d == 128 and rng.random() < 0.3) else d
+        Bn, H = int(rng.integers(1, 3)), int(rng.choice([1, 2, 3, 5, 8, 12, 20]))
+        N = int(rng.choice([2000, 3333, 4096, 6000, 9999, 16384]))
+        out16 = bool(rng.random() < 0.3)
+        cases.append((i, Bn, H, N, d, dv, dtype, out16))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_planned_cases(12), ids=lambda c: "n%d_B%d_H%d_N%d_r%d_dv%d_%s_o%d" % c)
+def test_random_longer_shapes_under_the_planner(B, case):
+    """Longer sequences with few to some heads: whatever (kernel, segment count) the planner picks
+    (many segments of either kernel), with an entering state and the final state checked."""
+    i, Bn, H, N, d, dv, dtype, out16 = case
+    code = B.LEET_BF16 if dtype == "bf16" else B.LEET_F16
+    say(f"case planned {case} plan (segments, kernel)={B.query_plan_rd(Bn, H, N, d, dv, code)}")
+    rng = np.random.default_rng(300 + i)
+    gamma = torch.from_numpy((1.0 - 2.0 ** -rng.uniform(2.0, 10.0, size=H)).astype(np.float32))
+    q, k, v, gamma = W.make_rd_forward_inputs(Bn, H, N, d, dv, dtype, seed=9000 + i, gamma=gamma)
+    s_in = torch.from_numpy((rng.standard_normal((Bn, H, d, dv)) * 0.02).astype(np.float32))
+    dq, dk, dvv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    S = torch.empty(Bn, H, d, dv, dtype=torch.float32, device="cuda")
+    odt = W.torch_dtype(dtype) if out16 else torch.float32
+    out = B.leet_attn_forward_rd(dq, dk, dvv, dg, state_in=ds_in, state_out=S, out_dtype=odt)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
+    check(to_np(out), ref, TOL[dtype], "out")
+    check(to_np(S), s_ref, TOL[dtype], "final state")

@@ -187,7 +187,9 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segment
         want = segments;
     } else {
         want = (kTargetWorkgroups + BH - 1) / BH;
-        long cap = nchunks / kMinSegChunksF32;
+        // short sequences (up to 32 chunks) are cut down to single chunks: the pre-pass and the scan
+        // cost less than a second chunk's MFMA latency in every workgroup (N = 512, d = 128: 28 against 43 us)
+        long cap = nchunks <= 32 ? nchunks : nchunks / kMinSegChunksF32;
         if (cap < 1) cap = 1;
         if (want > cap) want = cap;
     }

@@ -52,7 +52,8 @@ def test_workspace_bytes_plan(lib):
     from paper_2501_02573_amd import binding as b
     # one segment -> no workspace
     assert b.workspace_bytes(1, 1, 64, 64, b.LEET_F32) == 0
-    assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == 64 * 64 * 4  # fp32: segments of two chunks
+    assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == 3 * 64 * 64 * 4  # fp32, short sequence: four segments of one chunk
+    assert b.workspace_bytes(1, 1, 8192, 64, b.LEET_F32) == 63 * 64 * 64 * 4  # fp32, long sequence: segments of two chunks
     assert b.workspace_bytes(1, 1, 256, 64, b.LEET_BF16) == 0
     assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 1) == 0
     # s segments -> (s-1) boundary states of d*d floats per (b,h)

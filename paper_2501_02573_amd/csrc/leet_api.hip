@@ -97,9 +97,9 @@ constexpr int kCoopSlots = 256;               // one column-split workgroup per 
 double smooth_max(double a, double b, double p) { return pow(pow(a, p) + pow(b, p), 1.0 / p); }
 
 // nseg is a segment count that make_plan has already rounded (nseg = ceil(nchunks / seg_chunks))
-double predicted_us(bool coop, long BH, int N, int D, int DV, bool out16, int nseg, int seg_chunks) {
+double predicted_us(bool coop, long BH, int N, int D, int DV, int nseg, int seg_chunks) {
     const CostModel& m = D == 64 ? kCost64 : DV == 128 ? kCost128 : kCost128x256;
-    const double in_bytes = (double)BH * N * (2 * D + DV) * 2, out_bytes = (double)BH * N * DV * (out16 ? 2 : 4);
+    const double in_bytes = (double)BH * N * (2 * D + DV) * 2, out_bytes = (double)BH * N * DV * 4;
     // share of the inputs that no longer stays in the last-level cache: none up to 0.6 of its size
     // (the outputs pass through it too), all from 1.2
     const double spill = fmin(1.0, fmax(0.0, (in_bytes / (double)kLastLevelCacheBytes - 0.6) / 0.6));
@@ -128,14 +128,15 @@ double predicted_us(bool coop, long BH, int N, int D, int DV, bool out16, int ns
     return fmax(kThreeKernelFloorUs, m.three_kernel_us + walk + pre + scan * split);
 }
 
-// out16: the output is written in the (16-bit) input type
 // D: width of q and k rows (rank); DV: width of v and out rows
 //
 // 16-bit inputs: every eligible (kernel, segment count) pair is priced with the cost model
 // and the cheapest taken (ties go to fewer segments, then to the column-split kernel).  A caller's
 // segment count or kernel choice narrows the candidates.  fp32 keeps the rule of
-// about one workgroup per compute unit with a minimum segment length.
-bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segments, Plan* plan) {
+// about one workgroup per compute unit with a minimum segment length.  The plan depends on the
+// shape, the input type, the segment request and the kernel knob only -- not on the output type or
+// the mask -- so that leet_attn_workspace_bytes always sizes the workspace the call will ask for.
+bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
     const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
     const bool coop_able = dtype != LEET_F32;  // the column-split kernel: 16-bit inputs, every supported shape
@@ -171,7 +172,7 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, bool out16, int segment
             if (segments == 0 && nseg > 1 && seg_chunks < 2) break;
             for (int c = 1; c >= 0; --c) {
                 if (c ? !try_coop : !try_wide) continue;
-                const double t = predicted_us(c != 0, BH, N, D, DV, out16, nseg, seg_chunks);
+                const double t = predicted_us(c != 0, BH, N, D, DV, nseg, seg_chunks);
                 if (!have || t < best * 0.98) {
                     have = true; best = t; best_coop = c != 0; best_nseg = nseg; best_chunks = seg_chunks;
                 }
@@ -270,7 +271,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dv, dtype, out_dtype != LEET_F32, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dv, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -435,7 +436,7 @@ size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtyp
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, r, dv, dtype, false, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, r, dv, dtype, segments, &plan)) return 0;
     return plan.ws_bytes;
 }
 
@@ -467,7 +468,7 @@ int leet_attn_query_plan_rd(int B, int H, int N, int r, int dv, int dtype, int s
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     if (!shape_ok(r, dv, dtype, &status)) return status;
     Plan plan;
-    if (!make_plan((long)B * H, N, r, dv, dtype, false, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan((long)B * H, N, r, dv, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;
     if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
     return LEET_OK;

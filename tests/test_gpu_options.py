@@ -482,3 +482,22 @@ def test_random_longer_shapes_under_the_planner(B, case):
     ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
     check(to_np(out), ref, TOL[dtype], "out")
     check(to_np(S), s_ref, TOL[dtype], "final state")
+
+
+@pytest.mark.parametrize("out16", [False, True])
+def test_caller_workspace_sized_by_the_query_fits_every_output_type(B, out16):
+    """The workspace query has no output-type argument: the size it reports must serve a call with
+    fp32 output and one with 16-bit output alike (the plan does not depend on the output type)."""
+    Bn, H, N, d = 1, 4, 4096, 128
+    nseg, _ = B.query_plan(Bn, H, N, d, B.LEET_BF16)
+    assert nseg > 1
+    need = B.workspace_bytes(Bn, H, N, d, B.LEET_BF16)
+    assert need > 0
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=61)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    out = B.leet_attn_forward_v2(dq, dk, dv, dg, workspace=ws, out_dtype=torch.bfloat16 if out16 else torch.float32)
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(to_np(out), ref, TOL["bf16"], "out with a caller workspace of the queried size")
+    with pytest.raises(B.LeetAttnError):   # one byte short is refused before anything is launched
+        B.leet_attn_forward_v2(dq, dk, dv, dg, workspace=ws[: need - 256], out_dtype=torch.bfloat16 if out16 else torch.float32)

@@ -25,8 +25,8 @@
  *   - The caller owns all buffers.  The library keeps no pointer after the work
  *     is done.  `out` must not overlap any input.
  *   - The return value is a leet_status.  Arguments are validated on the host
- *     before anything is enqueued: on LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED and
- *     LEET_ERR_TOO_LARGE no buffer has been written.  LEET_ERR_LAUNCH means the HIP
+ *     before anything is enqueued: on every status but LEET_OK and
+ *     LEET_ERR_LAUNCH no buffer has been written.  LEET_ERR_LAUNCH means the HIP
  *     runtime failed part-way; the contents of the output buffers are then undefined.
  *   - d must be 64 or 128 (the _rd entry points also take rank 128 with value width
  *     256).  B, H, N >= 1.  N need not be a multiple of the chunk length (64
@@ -67,7 +67,9 @@ typedef enum {
     LEET_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, misaligned pointer, workspace too small */
     LEET_ERR_UNSUPPORTED = 2, /* d not in {64, 128}, unknown dtype or dtype combination, no gfx950 device */
     LEET_ERR_LAUNCH = 3,      /* the HIP runtime refused a launch or an allocation */
-    LEET_ERR_TOO_LARGE = 4    /* sizes overflow the library's index range */
+    LEET_ERR_TOO_LARGE = 4,   /* sizes overflow the library's index range */
+    LEET_ERR_CAPTURE = 5      /* `stream` is capturing and the library-owned workspace would have to be
+                                 allocated or grown; nothing was enqueued */
 } leet_status;
 
 /*
@@ -77,10 +79,16 @@ typedef enum {
  *   out      [B][H][N][d] float (fp32 for both input types)
  * Long sequences are cut into segments that run in parallel; the segment
  * boundary states live in a per-device workspace that the library allocates
- * with hipMalloc on first need and grows when a later call needs more (see
- * leet_attn_release_workspace).  Because that workspace is shared, calls on one
- * device must not run concurrently on different streams; use leet_attn_forward_ex
- * with caller-owned workspaces for that.
+ * with hipMalloc on first need.  When a later call needs more, a larger block
+ * is allocated and the old one is kept (work in flight or a captured graph may
+ * still use it) until leet_attn_release_workspace.  Because that workspace is
+ * shared, calls on one device must not run concurrently on different streams;
+ * use leet_attn_forward_ex with caller-owned workspaces for that.
+ * Under stream capture the library never allocates: if the workspace it owns
+ * is too small for the call the status is LEET_ERR_CAPTURE and nothing is
+ * recorded.  Make one eager call of the same shape before capturing (the graph
+ * then holds an address that stays valid until leet_attn_release_workspace), or
+ * capture leet_attn_forward_ex with a caller-owned workspace.
  */
 int leet_attn_forward(const void *q, const void *k, const void *v, const float *gamma, float *out,
                       int B, int H, int N, int d, int dtype, void *stream);
@@ -107,7 +115,9 @@ int leet_attn_decode_step_ex(const void *q, const void *k, const void *v, const 
  * continued by decode steps.
  *   state_in   [B][H][d][d] float or NULL (zero state); the state before token 0
  *   state_out  [B][H][d][d] float or NULL; receives the state after token N-1.
- *              May alias state_in.
+ *              May alias state_in (when the sequences are cut into segments the kernels read
+ *              the entering state from a copy in the workspace, so the order in which the
+ *              segments run does not matter).
  *   workspace  device buffer of at least leet_attn_workspace_bytes(B, H, N, d, dtype)
  *              bytes, 256-byte aligned, or NULL to use the library's own per-device
  *              workspace as leet_attn_forward does.  Its contents are scratch.
@@ -135,6 +145,7 @@ int leet_attn_forward_v2(const void *q, const void *k, const void *v, const floa
                          const float *state_in, float *state_out,
                          void *workspace, size_t workspace_bytes, int segments,
                          int B, int H, int N, int d, int in_dtype, int out_dtype, int mask, void *stream);
+
 
 /*
  * Row-based prefill: the same operator evaluated token by token as Alg. 1 (Appendix B.1) states
@@ -197,46 +208,19 @@ int leet_attn_decode_step_v2(const void *q, const void *k, const void *v, const 
                              void *stream);
 
 /*
- * Measurement aid: computes what leet_attn_forward_ex computes, with HIP events recorded on
- * `stream` around each of the three kernels a prefill launches; the call waits for them.
- * The pre-pass and the walk (which write the same values each time) are launched five times
- * back to back between their events and the time is divided by five; the scan runs once.
- *   kernel_ms  HOST pointer to 3 floats, filled with the milliseconds per launch of
- *              [0] the segment-state pre-pass, [1] the segment scan, [2] the chunk walk
- *              ([0] and [1] are 0 when the plan has a single segment).
- * Synchronous (returns after the work has finished); not for use under graph capture.
- */
-int leet_attn_forward_profile(const void *q, const void *k, const void *v, const float *gamma, float *out,
-                              const float *state_in, float *state_out,
-                              void *workspace, size_t workspace_bytes, int segments,
-                              int B, int H, int N, int d, int dtype, void *stream,
-                              float *kernel_ms);
-
-/*
- * Measurement aid: a plain streaming kernel of known traffic, used to calibrate the
- * profiler's HBM byte counters and to find the practical streaming rate of the device.
- *   mode 0  copy: reads `bytes` from src, writes `bytes` to dst
- *   mode 1  read: reads `bytes` from src; dst receives one float per workgroup
- *           (dst must hold `workgroups` floats)
- *   mode 2  fill: writes `bytes` to dst (src ignored)
- *   mode 3  copy, mode 4  fill, with nontemporal stores (how the library writes its outputs)
- *   bytes   multiple of 16; src, dst 16-byte aligned device pointers
- *   workgroups  grid size (256 threads each); each thread strides over the buffer
- * Asynchronous on `stream`.  Not part of the attention path.
- */
-int leet_attn_calibration_stream(int mode, const void *src, void *dst, size_t bytes, int workgroups,
-                                 void *stream);
-
-/*
  * Bytes of workspace leet_attn_forward_ex needs for this shape with `segments`
- * as above (0 = library's choice).  Returns 0 when no workspace is needed or the
- * arguments are invalid.
+ * as above (0 = library's choice) under the process-wide kernel choice: one d x d
+ * fp32 state per segment boundary the library computes, plus one per sequence for
+ * the copy of the entering state.  Returns 0 when no workspace is needed (one
+ * segment) or the arguments are invalid.
  */
 size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments);
 
 /*
- * Frees the library-owned workspace of the current device (synchronises the
- * device first).  Optional; the workspace is otherwise kept until process exit.
+ * Frees the library-owned workspace of the current device, including blocks retired
+ * when it grew (synchronises the device first).  Optional; the workspace is
+ * otherwise kept until process exit.  A graph captured from a call that used the
+ * library-owned workspace must not be replayed after this.
  */
 int leet_attn_release_workspace(void);
 
@@ -251,8 +235,10 @@ int leet_attn_release_workspace(void);
  *                             count with a cost model fitted to measurements and takes the
  *                             cheapest pair; leet_attn_query_plan reports the outcome
  * With WIDE or COLUMN_SPLIT set, only the segment count is chosen that way.
- * Process-wide; takes effect for calls made after it returns.  Returns LEET_ERR_INVALID_ARG for
- * any other value.
+ * The setter changes the process-wide default, which every entry point without a `kernel`
+ * argument uses; a thread that must not depend on what other threads set between its workspace
+ * query and its call passes the choice per call (the _v3 entry points below).  Returns
+ * LEET_ERR_INVALID_ARG for any other value.
  */
 typedef enum { LEET_KERNEL_WIDE = 0, LEET_KERNEL_COLUMN_SPLIT = 1, LEET_KERNEL_AUTO = 2 } leet_bf16_kernel;
 int leet_attn_set_bf16_kernel(int which);
@@ -260,23 +246,47 @@ int leet_attn_get_bf16_kernel(void);
 
 /*
  * Tuning knob: how a decode step stores the updated state.
- *   LEET_DECODE_STORE_AUTO    (default) streamed when this call's state exceeds half of the 256 MB
- *                             last-level cache, cached otherwise
+ *   LEET_DECODE_STORE_AUTO    (default) streamed when this call's state is a quarter of the 256 MB
+ *                             last-level cache or more, cached otherwise.  The library cannot see
+ *                             whether other states are stepped in between; streaming a state that
+ *                             would have stayed cached costs about 5 %, caching one that is
+ *                             displaced before its next step about 20 %
  *   LEET_DECODE_STORE_CACHED  ordinary stores: best when the next step on the same state finds it
  *                             in the cache (one small model stepping alone)
  *   LEET_DECODE_STORE_STREAM  nontemporal stores: best when other states are touched before this one
  *                             is used again (many layers taking turns), whatever its size
- * The results are identical; only the memory traffic differs.  Process-wide.
+ * The results are identical; only the memory traffic differs.  The setter changes the
+ * process-wide default; leet_attn_decode_step_v3 takes the policy per call.
  */
 typedef enum { LEET_DECODE_STORE_AUTO = 0, LEET_DECODE_STORE_CACHED = 1, LEET_DECODE_STORE_STREAM = 2 } leet_decode_store;
 int leet_attn_set_decode_store(int mode);
 int leet_attn_get_decode_store(void);
 
 /*
+ * Every choice per call.  `kernel` is a leet_bf16_kernel value and `store` a leet_decode_store
+ * value, or LEET_CHOICE_DEFAULT for the process-wide setting; everything else as in
+ * leet_attn_forward_rd, leet_attn_workspace_bytes_rd, leet_attn_query_plan_rd and
+ * leet_attn_decode_step_rd.  A caller that passes the same `kernel` and `segments` to
+ * leet_attn_workspace_bytes_v3 and to leet_attn_forward_v3 gets a workspace size that matches
+ * the call whatever other threads do with the setters.
+ */
+#define LEET_CHOICE_DEFAULT (-1)
+int leet_attn_forward_v3(const void *q, const void *k, const void *v, const float *gamma, void *out,
+                         const float *state_in, float *state_out,
+                         void *workspace, size_t workspace_bytes, int segments, int kernel,
+                         int B, int H, int N, int r, int dv, int in_dtype, int out_dtype, int mask, void *stream);
+size_t leet_attn_workspace_bytes_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel);
+int leet_attn_query_plan_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel_choice,
+                            int *nseg, int *kernel);
+int leet_attn_decode_step_v3(const void *q, const void *k, const void *v, const float *gamma,
+                             float *state_inout, float *out, int B, int H, int r, int dv, int dtype, int mask,
+                             int store, void *stream);
+
+/*
  * What leet_attn_forward_ex would do for this shape under the current kernel choice (fp32
- * output, decaying mask): *nseg receives the number of segments per sequence, *kernel
- * LEET_KERNEL_WIDE or LEET_KERNEL_COLUMN_SPLIT (for fp32 and fp16 inputs always WIDE).  Either
- * pointer may be NULL.  Host-only; touches no device.
+ * output, decaying mask; the plan depends on neither): *nseg receives the number of segments per
+ * sequence, *kernel LEET_KERNEL_WIDE or LEET_KERNEL_COLUMN_SPLIT (fp32 inputs always run WIDE;
+ * both 16-bit types have both kernels).  Either pointer may be NULL.  Host-only; touches no device.
  */
 int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int *nseg, int *kernel);
 /* The same for rank r and value width dv given separately (shapes as for leet_attn_forward_rd). */

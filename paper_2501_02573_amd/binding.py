@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libleet_attn.so")
 LEET_F32, LEET_BF16, LEET_F16 = 0, 1, 2
 LEET_MASK_DECAY, LEET_MASK_CAUSAL = 0, 1
 LEET_OK, LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED, LEET_ERR_LAUNCH, LEET_ERR_TOO_LARGE = 0, 1, 2, 3, 4
+LEET_ERR_CAPTURE = 5
+LEET_CHOICE_DEFAULT = -1
 
 EXPORTED_SYMBOLS = (
     "leet_attn_forward",
@@ -34,6 +36,10 @@ EXPORTED_SYMBOLS = (
     "leet_attn_forward_fleet",
     "leet_attn_decode_step_rd",
     "leet_attn_workspace_bytes_rd",
+    "leet_attn_forward_v3",
+    "leet_attn_workspace_bytes_v3",
+    "leet_attn_query_plan_v3",
+    "leet_attn_decode_step_v3",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
@@ -82,6 +88,14 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_decode_step_rd.restype = i
     lib.leet_attn_workspace_bytes_rd.argtypes = [i, i, i, i, i, i, i]
     lib.leet_attn_workspace_bytes_rd.restype = sz
+    lib.leet_attn_forward_v3.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_v3.restype = i
+    lib.leet_attn_workspace_bytes_v3.argtypes = [i, i, i, i, i, i, i, i]
+    lib.leet_attn_workspace_bytes_v3.restype = sz
+    lib.leet_attn_query_plan_v3.argtypes = [i, i, i, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.leet_attn_query_plan_v3.restype = i
+    lib.leet_attn_decode_step_v3.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.leet_attn_decode_step_v3.restype = i
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
@@ -459,6 +473,47 @@ def leet_attn_forward_rd(q, k, v, gamma: Optional[torch.Tensor], out: Optional[t
     return out
 
 
+def leet_attn_forward_v3(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
+                         state_in: Optional[torch.Tensor] = None, state_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, segments: int = 0,
+                         kernel: int = LEET_CHOICE_DEFAULT,
+                         out_dtype: Optional[torch.dtype] = None, mask: int = LEET_MASK_DECAY) -> torch.Tensor:
+    """``leet_attn_forward_rd`` with the kernel choice given per call."""
+    if out is None:
+        out = torch.empty(v.shape, dtype=out_dtype or torch.float32, device=v.device)
+    B, H, N, r, dv = _check_rd(q, k, v, gamma, out, True)
+    _check_states_rd(B, H, r, dv, state_in=state_in, state_out=state_out)
+    ws_bytes = 0
+    if workspace is not None:
+        if workspace.dtype != torch.uint8:
+            raise TypeError("workspace must be a uint8 tensor")
+        ws_bytes = workspace.numel()
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out, workspace)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_v3(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                      _ptr(state_out), _ptr(workspace), ws_bytes, int(segments), int(kernel),
+                                      B, H, N, r, dv, _dtype_code(q), _dtype_code(out), int(mask),
+                                      ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_v3")
+    return out
+
+
+def workspace_bytes_v3(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments: int = 0,
+                       kernel: int = LEET_CHOICE_DEFAULT) -> int:
+    return int(lib.leet_attn_workspace_bytes_v3(B, H, N, r, dv, dtype, segments, kernel))
+
+
+def query_plan_v3(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments: int = 0,
+                  kernel: int = LEET_CHOICE_DEFAULT):
+    """``query_plan_rd`` with the kernel choice given per call."""
+    nseg, kern = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib.leet_attn_query_plan_v3(B, H, N, r, dv, dtype, segments, kernel, ctypes.byref(nseg), ctypes.byref(kern))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_query_plan_v3")
+    return nseg.value, kern.value
+
+
 def leet_attn_forward_recurrent_rd(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
                                    state_in: Optional[torch.Tensor] = None,
                                    state_out: Optional[torch.Tensor] = None,
@@ -498,8 +553,11 @@ def leet_attn_forward_fleet(q, k, v, gamma: Optional[torch.Tensor], out: Optiona
 
 
 def leet_attn_decode_step_rd(q, k, v, gamma: Optional[torch.Tensor], state, out: Optional[torch.Tensor] = None,
-                             mask: int = LEET_MASK_DECAY) -> torch.Tensor:
-    """One decode step with q, k [B, H, r], v [B, H, dv] and state [B, H, r, dv] (updated in place)."""
+                             mask: int = LEET_MASK_DECAY, store: Optional[int] = None) -> torch.Tensor:
+    """One decode step with q, k [B, H, r], v [B, H, dv] and state [B, H, r, dv] (updated in place).
+
+    ``store`` (a DECODE_STORE_* value) routes the call through ``leet_attn_decode_step_v3``, which takes
+    the state store policy per call."""
     if q.dim() != 3 or q.shape != k.shape or v.dim() != 3 or q.shape[:2] != v.shape[:2]:
         raise ValueError("q, k must share one [B, H, r] shape and v be [B, H, dv]")
     if k.dtype != q.dtype or v.dtype != q.dtype:
@@ -515,8 +573,13 @@ def leet_attn_decode_step_rd(q, k, v, gamma: Optional[torch.Tensor], state, out:
         raise ValueError("out must be float32 [B, H, dv]")
     dev = _check_dev(q, k, v, gamma, state, out)
     with torch.cuda.device(dev):
-        st = lib.leet_attn_decode_step_rd(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
-                                          B, H, r, dv, _dtype_code(q), int(mask), ctypes.c_void_p(_stream_ptr(dev)))
+        if store is None:
+            st = lib.leet_attn_decode_step_rd(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                              B, H, r, dv, _dtype_code(q), int(mask), ctypes.c_void_p(_stream_ptr(dev)))
+        else:
+            st = lib.leet_attn_decode_step_v3(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(state), _ptr(out),
+                                              B, H, r, dv, _dtype_code(q), int(mask), int(store),
+                                              ctypes.c_void_p(_stream_ptr(dev)))
     if st != LEET_OK:
-        raise LeetAttnError(st, "leet_attn_decode_step_rd")
+        raise LeetAttnError(st, "leet_attn_decode_step_v3" if store is not None else "leet_attn_decode_step_rd")
     return out

@@ -5,8 +5,10 @@
 #include <mutex>
 #include <stdlib.h>
 #include <string.h>
+#include <vector>
 
 #include "../../include/leet_attn.h"
+#include "../../include/leet_attn_bench.h"
 #include "leet_common.hpp"
 
 namespace leet {
@@ -16,7 +18,7 @@ hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, int D
 hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
 hipError_t launch_fwd_f32_walk(const FwdParams& p, int BH, int D, hipStream_t stream);
-hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
+hipError_t launch_seg_scan(float* seg_state, const float* state_in, float* state_copy, const float* gamma, int BH, int H,
                            int nseg, int seg_tokens, int step, int D, int DV, hipStream_t stream);
 hipError_t launch_recurrent(const void* q, const void* k, const void* v, const float* gamma, float* out,
                             const float* state_in, float* state_out, int BH, int H, int N, int D, int DV,
@@ -43,11 +45,16 @@ constexpr int kMinSegChunksF32 = 2;
 constexpr int kMaxDevices = 64;
 constexpr size_t kLastLevelCacheBytes = (size_t)256 << 20;  // MI355X Infinity Cache
 
+// Process-wide defaults of the two tuning knobs, used by every entry point that does not take the
+// choice as an argument (and by the _v3 ones when they are passed LEET_CHOICE_DEFAULT).
 // Kernel choice for 16-bit prefill (bf16 and fp16; the name is historical): a leet_bf16_kernel value.
 std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
 
 // Decode-state store policy: a leet_decode_store value.
 std::atomic<int> g_decode_store{LEET_DECODE_STORE_AUTO};
+
+bool kernel_choice_ok(int c) { return c == LEET_KERNEL_WIDE || c == LEET_KERNEL_COLUMN_SPLIT || c == LEET_KERNEL_AUTO; }
+bool decode_store_ok(int m) { return m == LEET_DECODE_STORE_AUTO || m == LEET_DECODE_STORE_CACHED || m == LEET_DECODE_STORE_STREAM; }
 
 struct Plan {
     int nseg;
@@ -136,9 +143,10 @@ double predicted_us(bool coop, long BH, int N, int D, int DV, int nseg, int seg_
 // about one workgroup per compute unit with a minimum segment length.  The plan depends on the
 // shape, the input type, the segment request and the kernel knob only -- not on the output type or
 // the mask -- so that leet_attn_workspace_bytes always sizes the workspace the call will ask for.
-bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, Plan* plan) {
+// choice: a leet_bf16_kernel value, or LEET_CHOICE_DEFAULT for the process-wide setting.
+bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, int choice, Plan* plan) {
     const int nchunks = (N + kChunk - 1) / kChunk;
-    const int choice = g_bf16_kernel.load(std::memory_order_relaxed);
+    if (choice == LEET_CHOICE_DEFAULT) choice = g_bf16_kernel.load(std::memory_order_relaxed);
     const bool coop_able = dtype != LEET_F32;  // the column-split kernel: 16-bit inputs, every supported shape
     auto finish = [&](bool coop, int nseg, int seg_chunks) {
         const long per_seg = coop ? BH * (DV / 32) : BH;  // workgroups one segment of every sequence gives
@@ -147,7 +155,10 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, Plan* pla
         plan->nseg = nseg;
         plan->seg_chunks = seg_chunks;
         plan->pre_split = (dtype != LEET_F32 && !coop) ? wide_pre_split(BH, nseg, seg_chunks) : 1;
-        plan->ws_bytes = (size_t)BH * (size_t)(nseg - 1) * plan->pre_split * D * DV * sizeof(float);
+        // one state per boundary the pre-pass computes, and, with segments, one more per sequence:
+        // the scan's copy of the entering state, which the walk reads instead of the caller's buffer
+        const size_t slots = nseg > 1 ? (size_t)(nseg - 1) * plan->pre_split + 1 : 0;
+        plan->ws_bytes = (size_t)BH * slots * D * DV * sizeof(float);
         return true;
     };
     auto round_segments = [&](long want, int* nseg, int* seg_chunks) {
@@ -212,10 +223,14 @@ bool shape_ok(int d, int dv, int dtype, int* status) {
 }
 bool shape_ok(int d, int dtype, int* status) { return shape_ok(d, d, dtype, status); }
 
-// Library-owned workspace, one per device, grown on demand.
+// Library-owned workspace, one per device, grown on demand.  A block that a call has handed to
+// a launch is never freed behind the caller's back: work still in flight, or a captured graph that
+// is replayed later, may hold its address.  When a later call needs more, a larger block is
+// allocated and the old one is retired until leet_attn_release_workspace.
 std::mutex g_ws_mutex;
 void* g_ws_ptr[kMaxDevices] = {nullptr};
 size_t g_ws_size[kMaxDevices] = {0};
+std::vector<void*> g_ws_retired[kMaxDevices];
 int g_arch_ok[kMaxDevices] = {0};  // 0 unknown, 1 gfx950, -1 other
 
 int current_device(int* dev) {
@@ -230,21 +245,33 @@ int current_device(int* dev) {
     return g_arch_ok[*dev] == 1 ? LEET_OK : LEET_ERR_UNSUPPORTED;
 }
 
-int own_workspace(int dev, size_t bytes, void** out) {
+int own_workspace(int dev, size_t bytes, hipStream_t stream, void** out) {
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (g_ws_size[dev] < bytes) {
-        if (g_ws_ptr[dev]) {
-            (void)hipFree(g_ws_ptr[dev]);  // waits for work that may still use it
-            g_ws_ptr[dev] = nullptr;
-            g_ws_size[dev] = 0;
+        // Growing means hipMalloc, which must not happen inside a stream capture (and the graph
+        // would keep an address that only this capture's call ever sized).
+        if (stream) {
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(stream, &cs) != hipSuccess) {
+                (void)hipGetLastError();
+                return LEET_ERR_LAUNCH;
+            }
+            if (cs != hipStreamCaptureStatusNone) return LEET_ERR_CAPTURE;
         }
+        // at least double, so that a run of growing shapes retires few blocks
+        size_t want = bytes > 2 * g_ws_size[dev] ? bytes : 2 * g_ws_size[dev];
         void* p = nullptr;
-        if (hipMalloc(&p, bytes) != hipSuccess) {
+        if (hipMalloc(&p, want) != hipSuccess) {
             (void)hipGetLastError();
-            return LEET_ERR_LAUNCH;
+            want = bytes;
+            if (hipMalloc(&p, want) != hipSuccess) {
+                (void)hipGetLastError();
+                return LEET_ERR_LAUNCH;
+            }
         }
+        if (g_ws_ptr[dev]) g_ws_retired[dev].push_back(g_ws_ptr[dev]);
         g_ws_ptr[dev] = p;
-        g_ws_size[dev] = bytes;
+        g_ws_size[dev] = want;
     }
     *out = g_ws_ptr[dev];
     return LEET_OK;
@@ -253,8 +280,9 @@ int own_workspace(int dev, size_t bytes, void** out) {
 int forward_impl(const void* q, const void* k, const void* v, const float* gamma, void* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
                  int segments, int B, int H, int N, int d, int dv, int dtype, int out_dtype, int mask,
-                 void* stream, float* kernel_ms) {
+                 void* stream, float* kernel_ms, int kernel_choice = LEET_CHOICE_DEFAULT) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
+    if (kernel_choice != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel_choice)) return LEET_ERR_INVALID_ARG;
     const bool no_decay = mask == LEET_MASK_CAUSAL;
     if (!q || !k || !v || !out || (!gamma && !no_decay)) return LEET_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
@@ -271,10 +299,14 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
 
     Plan plan;
-    if (!make_plan(BH, N, d, dv, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan(BH, N, d, dv, dtype, segments, kernel_choice, &plan)) return LEET_ERR_TOO_LARGE;
+    // the timing aid relaunches the walk: with the state handed on in place, later launches would
+    // start from the state the first one left
+    if (kernel_ms && state_in && state_in == state_out) return LEET_ERR_INVALID_ARG;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
+    hipStream_t s = static_cast<hipStream_t>(stream);
 
     void* ws = nullptr;
     if (plan.nseg > 1) {
@@ -282,7 +314,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
             if (workspace_bytes < plan.ws_bytes) return LEET_ERR_INVALID_ARG;
             ws = workspace;
         } else {
-            status = own_workspace(dev, plan.ws_bytes, &ws);
+            status = own_workspace(dev, plan.ws_bytes, s, &ws);
             if (status != LEET_OK) return status;
         }
     }
@@ -294,6 +326,15 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     p.H = H; p.N = N; p.nseg = plan.nseg; p.seg_chunks = plan.seg_chunks;
     p.state_slots = (plan.nseg - 1) * plan.pre_split;
     p.state_step = plan.pre_split;
+    // With segments, the first segments of the walk read the entering state from the scan's copy
+    // of it (the slots after all boundary states), never from the caller's buffer: state_out may
+    // alias state_in, and the last segment of a sequence may finish, and write it, before the
+    // first segment of the same sequence has started.
+    float* state_copy = nullptr;
+    if (plan.nseg > 1 && state_in) {
+        state_copy = p.seg_state + (size_t)BH * p.state_slots * d * dv;
+        p.state_in = state_copy;
+    }
     p.no_decay = no_decay ? 1 : 0;
     // Inputs that fit the 256 MB last-level cache are left to it (a pre-pass reads K and V before
     // the walk does, and a caller's next layer may reuse them); larger ones are streamed.
@@ -301,7 +342,6 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     leet::FwdParams pre = p;  // geometry of the pre-pass and of the scan
     pre.nseg = p.state_slots + 1;
     pre.seg_chunks = plan.seg_chunks / plan.pre_split;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const bool in16 = dtype != LEET_F32;
     const bool f16 = dtype == LEET_F16;
     const bool out16 = out_dtype != LEET_F32;
@@ -313,7 +353,8 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
                       : leet::launch_fwd_f32_states(p, (int)BH, d, s);
     };
     auto launch_scan = [&]() {
-        return leet::launch_seg_scan(p.seg_state, state_in, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk, p.state_step, d, dv, s);
+        return leet::launch_seg_scan(p.seg_state, state_in, state_copy, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk,
+                                     p.state_step, d, dv, s);
     };
     auto launch_walk = [&]() {
         return coop   ? leet::launch_fwd_16bit_coop_walk(p, (int)BH, d, dv, f16, out16, s)
@@ -432,12 +473,25 @@ int leet_attn_forward_rd(const void* q, const void* k, const void* v, const floa
                         B, H, N, r, dv, in_dtype, out_dtype, mask, stream, nullptr);
 }
 
-size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtype, int segments) {
+int leet_attn_forward_v3(const void* q, const void* k, const void* v, const float* gamma, void* out,
+                         const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
+                         int segments, int kernel, int B, int H, int N, int r, int dv, int in_dtype,
+                         int out_dtype, int mask, void* stream) {
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, workspace, workspace_bytes, segments,
+                        B, H, N, r, dv, in_dtype, out_dtype, mask, stream, nullptr, kernel);
+}
+
+size_t leet_attn_workspace_bytes_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel) {
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
+    if (kernel != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel)) return 0;
     Plan plan;
-    if (!make_plan((long)B * H, N, r, dv, dtype, segments, &plan)) return 0;
+    if (!make_plan((long)B * H, N, r, dv, dtype, segments, kernel, &plan)) return 0;
     return plan.ws_bytes;
+}
+
+size_t leet_attn_workspace_bytes_rd(int B, int H, int N, int r, int dv, int dtype, int segments) {
+    return leet_attn_workspace_bytes_v3(B, H, N, r, dv, dtype, segments, LEET_CHOICE_DEFAULT);
 }
 
 size_t leet_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int segments) {
@@ -463,25 +517,32 @@ int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, con
                                           stream);
 }
 
-int leet_attn_query_plan_rd(int B, int H, int N, int r, int dv, int dtype, int segments, int* nseg, int* kernel) {
+int leet_attn_query_plan_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel_choice,
+                            int* nseg, int* kernel) {
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    if (kernel_choice != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel_choice)) return LEET_ERR_INVALID_ARG;
     if (!shape_ok(r, dv, dtype, &status)) return status;
     Plan plan;
-    if (!make_plan((long)B * H, N, r, dv, dtype, segments, &plan)) return LEET_ERR_TOO_LARGE;
+    if (!make_plan((long)B * H, N, r, dv, dtype, segments, kernel_choice, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;
     if (kernel) *kernel = plan.coop ? LEET_KERNEL_COLUMN_SPLIT : LEET_KERNEL_WIDE;
     return LEET_OK;
+}
+
+int leet_attn_query_plan_rd(int B, int H, int N, int r, int dv, int dtype, int segments, int* nseg, int* kernel) {
+    return leet_attn_query_plan_v3(B, H, N, r, dv, dtype, segments, LEET_CHOICE_DEFAULT, nseg, kernel);
 }
 
 int leet_attn_query_plan(int B, int H, int N, int d, int dtype, int segments, int* nseg, int* kernel) {
     return leet_attn_query_plan_rd(B, H, N, d, d, dtype, segments, nseg, kernel);
 }
 
-int leet_attn_decode_step_rd(const void* q, const void* k, const void* v, const float* gamma,
+int leet_attn_decode_step_v3(const void* q, const void* k, const void* v, const float* gamma,
                              float* state_inout, float* out, int B, int H, int d, int dv, int dtype, int mask,
-                             void* stream) {
+                             int store, void* stream) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
+    if (store != LEET_CHOICE_DEFAULT && !decode_store_ok(store)) return LEET_ERR_INVALID_ARG;
     if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
     if (!q || !k || !v || (!gamma && mask == LEET_MASK_DECAY) || !state_inout || !out) return LEET_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
@@ -497,16 +558,26 @@ int leet_attn_decode_step_rd(const void* q, const void* k, const void* v, const 
     status = current_device(&dev);
     if (status != LEET_OK) return status;
     const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
-    // AUTO: a state that fills more than half of the last-level cache will not be found there by
-    // the next step, so it is stored with the nontemporal hint (6.4 instead of 5.1 TB/s at 512 MiB);
-    // a smaller one is stored normally (a 128 MiB state stepped repeatedly: 39.9 against 41.8 us).
-    const int store_mode = g_decode_store.load(std::memory_order_relaxed);
+    // AUTO cannot see whether other states (other layers of a model) are touched before this one is
+    // stepped again, so it weighs the two mistakes: streaming a state that would have stayed in the
+    // last-level cache costs 5 % (128 MiB stepped alone: 41.8 against 39.9 us), caching one that is
+    // displaced before its next step costs 20 % (three 128 MiB states in turn: 53 against 44 us;
+    // 512 MiB: 6.4 against 5.1 TB/s).  A state of a quarter of that cache or more is therefore
+    // streamed; smaller ones, which also survive next to a few neighbours, are stored normally.
+    const int store_mode = store == LEET_CHOICE_DEFAULT ? g_decode_store.load(std::memory_order_relaxed) : store;
     const bool stream_store = store_mode == LEET_DECODE_STORE_STREAM ||
                               (store_mode == LEET_DECODE_STORE_AUTO &&
-                               (size_t)BH * d * dv * sizeof(float) > kLastLevelCacheBytes / 2);
+                               (size_t)BH * d * dv * sizeof(float) >= kLastLevelCacheBytes / 4);
     hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, dv, elem, stream_store,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
+int leet_attn_decode_step_rd(const void* q, const void* k, const void* v, const float* gamma,
+                             float* state_inout, float* out, int B, int H, int d, int dv, int dtype, int mask,
+                             void* stream) {
+    return leet_attn_decode_step_v3(q, k, v, gamma, state_inout, out, B, H, d, dv, dtype, mask, LEET_CHOICE_DEFAULT,
+                                    stream);
 }
 
 int leet_attn_decode_step_v2(const void* q, const void* k, const void* v, const float* gamma,
@@ -529,12 +600,16 @@ int leet_attn_release_workspace(void) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LEET_ERR_LAUNCH;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
+    int rc = LEET_OK;
     if (g_ws_ptr[dev]) {
-        if (hipFree(g_ws_ptr[dev]) != hipSuccess) return LEET_ERR_LAUNCH;
+        if (hipFree(g_ws_ptr[dev]) != hipSuccess) rc = LEET_ERR_LAUNCH;
         g_ws_ptr[dev] = nullptr;
         g_ws_size[dev] = 0;
     }
-    return LEET_OK;
+    for (void* old : g_ws_retired[dev])
+        if (hipFree(old) != hipSuccess) rc = LEET_ERR_LAUNCH;
+    g_ws_retired[dev].clear();
+    return rc;
 }
 
 const char* leet_attn_strerror(int status) {
@@ -544,13 +619,13 @@ const char* leet_attn_strerror(int status) {
         case LEET_ERR_UNSUPPORTED: return "unsupported (d must be 64 or 128, or rank 128 with value width 256 for 16-bit inputs; dtype f32, bf16 or f16; output fp32 or the 16-bit input type; device gfx950)";
         case LEET_ERR_LAUNCH: return "HIP runtime error (launch or allocation failed)";
         case LEET_ERR_TOO_LARGE: return "sizes exceed the library's index range";
+        case LEET_ERR_CAPTURE: return "the library-owned workspace would have to be allocated or grown while the stream is capturing (make one eager call of this size first, or pass a caller-owned workspace)";
         default: return "unknown status";
     }
 }
 
 int leet_attn_set_bf16_kernel(int which) {
-    if (which != LEET_KERNEL_WIDE && which != LEET_KERNEL_COLUMN_SPLIT && which != LEET_KERNEL_AUTO)
-        return LEET_ERR_INVALID_ARG;
+    if (!kernel_choice_ok(which)) return LEET_ERR_INVALID_ARG;
     g_bf16_kernel.store(which, std::memory_order_relaxed);
     return LEET_OK;
 }
@@ -558,14 +633,13 @@ int leet_attn_set_bf16_kernel(int which) {
 int leet_attn_get_bf16_kernel(void) { return g_bf16_kernel.load(std::memory_order_relaxed); }
 
 int leet_attn_set_decode_store(int mode) {
-    if (mode != LEET_DECODE_STORE_AUTO && mode != LEET_DECODE_STORE_CACHED && mode != LEET_DECODE_STORE_STREAM)
-        return LEET_ERR_INVALID_ARG;
+    if (!decode_store_ok(mode)) return LEET_ERR_INVALID_ARG;
     g_decode_store.store(mode, std::memory_order_relaxed);
     return LEET_OK;
 }
 
 int leet_attn_get_decode_store(void) { return g_decode_store.load(std::memory_order_relaxed); }
 
-const char* leet_attn_version(void) { return "0.5.0"; }
+const char* leet_attn_version(void) { return "0.6.0"; }
 
 }  // extern "C"

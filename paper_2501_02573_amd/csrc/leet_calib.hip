@@ -5,6 +5,7 @@
 // with nontemporal stores, which is how the library's own kernels write data they will not read
 // again.
 #include "../../include/leet_attn.h"
+#include "../../include/leet_attn_bench.h"
 #include "leet_common.hpp"
 
 namespace leet {

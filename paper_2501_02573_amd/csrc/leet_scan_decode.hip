@@ -14,9 +14,12 @@ namespace leet {
 // run on segments `step` times finer than the walk's, which reads no other boundary.
 // One thread per four state elements; the loop over segments is sequential.
 // gamma == nullptr means gamma = 1 for every head (0/1 causal mask).
+// state_copy (null, or [BH][D][DV]) receives state_in unchanged: the walk's first segments read the
+// entering state from there, so that the caller's buffer is read only by this kernel, which has
+// finished before any workgroup of the walk can write the leaving state to an aliased state_out.
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const float* state_in,
-                                                       const float* gamma, int H, int nseg,
+                                                       float* state_copy, const float* gamma, int H, int nseg,
                                                        int seg_tokens, int step, int DD4, size_t total4) {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total4) return;
@@ -24,7 +27,10 @@ __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const f
     int e4 = (int)(idx % DD4);
     const float gl = gamma ? (float)pow_int((double)gamma[bh % H], seg_tokens) : 1.0f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (state_in) acc = reinterpret_cast<const f32x4*>(state_in)[idx];
+    if (state_in) {
+        acc = reinterpret_cast<const f32x4*>(state_in)[idx];
+        if (state_copy) reinterpret_cast<f32x4*>(state_copy)[idx] = acc;
+    }
     f32x4* slot = reinterpret_cast<f32x4*>(seg_state) + (size_t)bh * (nseg - 1) * DD4 + e4;
     // eight slots at a time: their loads are independent and go out together
     constexpr int kBatch = 8;
@@ -43,13 +49,13 @@ __global__ __launch_bounds__(256) void seg_scan_kernel(float* seg_state, const f
 }
 
 // D x DV: shape of one state (rank x value width)
-hipError_t launch_seg_scan(float* seg_state, const float* state_in, const float* gamma, int BH, int H,
+hipError_t launch_seg_scan(float* seg_state, const float* state_in, float* state_copy, const float* gamma, int BH, int H,
                            int nseg, int seg_tokens, int step, int D, int DV, hipStream_t stream) {
     if (nseg <= 1) return hipSuccess;
     int DD4 = D * DV / 4;
     size_t total4 = (size_t)BH * DD4;
     unsigned blocks = (unsigned)((total4 + 255) / 256);
-    hipLaunchKernelGGL(seg_scan_kernel, dim3(blocks), dim3(256), 0, stream, seg_state, state_in, gamma, H,
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(blocks), dim3(256), 0, stream, seg_state, state_in, state_copy, gamma, H,
                        nseg, seg_tokens, step, DD4, total4);
     return hipGetLastError();
 }

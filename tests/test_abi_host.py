@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "leet_attn.h")
+HEADERS = [HEADER, os.path.join(ROOT, "include", "leet_attn_bench.h")]   # the boundary, and the measurement aids
 LIB = os.path.join(ROOT, "paper_2501_02573_amd", "libleet_attn.so")
 
 
@@ -20,30 +21,36 @@ def lib():
     return binding.lib
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(leet_attn_\w+)\s*\(", text)))
+def declared_functions(headers=HEADERS):
+    names = set()
+    for path in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names |= set(re.findall(r"\b(leet_attn_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_mandated_entry_points():
-    names = declared_functions()
+    names = declared_functions([HEADER])
     assert "leet_attn_forward" in names and "leet_attn_decode_step" in names
     assert len(names) >= 6
+    # the measurement aids are declared apart from the attention boundary
+    assert "leet_attn_forward_profile" not in names and "leet_attn_calibration_stream" not in names
+    assert set(declared_functions()) == set(names) | {"leet_attn_forward_profile", "leet_attn_calibration_stream"}
 
 
 def test_library_exports_every_declared_symbol(lib):
     from paper_2501_02573_amd import binding
     raw = ctypes.CDLL(LIB)
     for name in declared_functions():
-        assert hasattr(raw, name), f"{name} declared in leet_attn.h but not exported"
+        assert hasattr(raw, name), f"{name} declared in include/ but not exported"
         assert name in binding.EXPORTED_SYMBOLS
+    assert set(binding.EXPORTED_SYMBOLS) == set(declared_functions())
 
 
 def test_strerror_and_version(lib):
     from paper_2501_02573_amd import binding
     assert binding.strerror(0) == "ok"
-    for st in (1, 2, 3, 4, 99):
+    for st in (1, 2, 3, 4, 5, 99):
         assert len(binding.strerror(st)) > 0
     assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
 
@@ -52,15 +59,16 @@ def test_workspace_bytes_plan(lib):
     from paper_2501_02573_amd import binding as b
     # one segment -> no workspace
     assert b.workspace_bytes(1, 1, 64, 64, b.LEET_F32) == 0
-    assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == 3 * 64 * 64 * 4  # fp32, short sequence: four segments of one chunk
-    assert b.workspace_bytes(1, 1, 8192, 64, b.LEET_F32) == 63 * 64 * 64 * 4  # fp32, long sequence: segments of two chunks
+    # with segments: one state per boundary, plus one per sequence for the copy of the entering state
+    assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == (3 + 1) * 64 * 64 * 4  # fp32, short sequence: four segments of one chunk
+    assert b.workspace_bytes(1, 1, 8192, 64, b.LEET_F32) == (63 + 1) * 64 * 64 * 4  # fp32, long sequence: segments of two chunks
     assert b.workspace_bytes(1, 1, 256, 64, b.LEET_BF16) == 0
     assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 1) == 0
-    # s segments -> (s-1) boundary states of d*d floats per (b,h)
-    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 8) == 4 * 16 * 7 * 128 * 128 * 4
-    assert b.workspace_bytes(1, 32, 32768, 128, b.LEET_BF16, 16) == 32 * 15 * 128 * 128 * 4
+    # s segments -> (s-1) boundary states of d*d floats per (b,h), and the entering-state copy
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 8) == 4 * 16 * (7 + 1) * 128 * 128 * 4
+    assert b.workspace_bytes(1, 32, 32768, 128, b.LEET_BF16, 16) == 32 * (15 + 1) * 128 * 128 * 4
     # requests beyond the number of chunks are clamped: N=130 has 3 chunks
-    assert b.workspace_bytes(1, 1, 130, 64, b.LEET_F32, 50) == 2 * 64 * 64 * 4
+    assert b.workspace_bytes(1, 1, 130, 64, b.LEET_F32, 50) == (2 + 1) * 64 * 64 * 4
     # invalid shapes report 0
     assert b.workspace_bytes(1, 1, 256, 96, b.LEET_F32) == 0
     assert b.workspace_bytes(0, 1, 256, 64, b.LEET_F32) == 0
@@ -125,7 +133,7 @@ def test_kernel_choice_setter_and_plan_query(lib):
         b.set_bf16_kernel(b.KERNEL_WIDE)
         assert b.query_plan(4, 16, 4096, 128, b.LEET_BF16) == (4, b.KERNEL_WIDE)
         # four segments for the walk, boundary states on half-segments for the pre-pass and the scan
-        assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 4 * 16 * 6 * 128 * 128 * 4
+        assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16) == 4 * 16 * (6 + 1) * 128 * 128 * 4
         with pytest.raises(b.LeetAttnError):
             b.set_bf16_kernel(7)
         assert b.get_bf16_kernel() == b.KERNEL_WIDE
@@ -186,10 +194,11 @@ def test_planner_invariants_on_random_shapes(lib):
         state = B * H * d * d * 4
         assert ws % state == 0
         slots = ws // state
+        extra = 1 if nseg > 1 else 0    # the copy of the entering state
         if kern == b.KERNEL_COLUMN_SPLIT or dtype == b.LEET_F32:
-            assert slots == nseg - 1
+            assert slots == nseg - 1 + extra
         else:
-            assert slots in (nseg - 1, 2 * (nseg - 1))
+            assert slots in (nseg - 1 + extra, 2 * (nseg - 1) + extra)
 
 
 def test_binding_rejects_cpu_tensors(lib):
@@ -221,7 +230,39 @@ def test_header_is_plain_c(tmp_path):
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     src = tmp_path / "use_header.c"
     calls = "\n".join(f"    (void)&{name};" for name in b.EXPORTED_SYMBOLS)
-    src.write_text('#include "leet_attn.h"\nint main(void) {\n' + calls + "\n    return 0;\n}\n")
+    src.write_text('#include "leet_attn.h"\n#include "leet_attn_bench.h"\nint main(void) {\n' + calls + "\n    return 0;\n}\n")
     res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
                           "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
+
+
+def test_per_call_choices_match_the_setters(lib):
+    """The _v3 queries take the kernel choice as an argument: same answers as under the setter, and
+    independent of what the process-wide default is set to meanwhile."""
+    from paper_2501_02573_amd import binding as b
+    shapes = [(4, 16, 4096, 128, 128), (1, 32, 32768, 128, 128), (1, 1, 4096, 128, 128), (2, 3, 777, 64, 64),
+              (1, 32, 2048, 128, 256)]
+    try:
+        want = {}
+        for choice in (b.KERNEL_WIDE, b.KERNEL_COLUMN_SPLIT, b.KERNEL_AUTO):
+            b.set_bf16_kernel(choice)
+            for sh in shapes:
+                want[(choice, sh)] = (b.query_plan_rd(*sh[:3], sh[3], sh[4], b.LEET_BF16),
+                                      b.workspace_bytes_rd(*sh[:3], sh[3], sh[4], b.LEET_BF16))
+        for default in (b.KERNEL_WIDE, b.KERNEL_COLUMN_SPLIT, b.KERNEL_AUTO):
+            b.set_bf16_kernel(default)
+            for (choice, sh), (plan, ws) in want.items():
+                assert b.query_plan_v3(*sh[:3], sh[3], sh[4], b.LEET_BF16, 0, choice) == plan
+                assert b.workspace_bytes_v3(*sh[:3], sh[3], sh[4], b.LEET_BF16, 0, choice) == ws
+            for sh in shapes:   # LEET_CHOICE_DEFAULT follows the setter
+                assert b.query_plan_v3(*sh[:3], sh[3], sh[4], b.LEET_BF16) == want[(default, sh)][0]
+        with pytest.raises(b.LeetAttnError):
+            b.query_plan_v3(1, 1, 4096, 128, 128, b.LEET_BF16, 0, 9)
+        assert b.workspace_bytes_v3(1, 1, 4096, 128, 128, b.LEET_BF16, 0, 9) == 0
+    finally:
+        b.set_bf16_kernel(b.KERNEL_AUTO)
+    p = ctypes.c_void_p(0x1000)
+    assert lib.leet_attn_decode_step_v3(p, p, p, p, p, p, 1, 1, 64, 64, b.LEET_BF16, 0, 7, None) == b.LEET_ERR_INVALID_ARG
+    assert lib.leet_attn_forward_v3(p, p, p, p, p, None, None, None, 0, 0, 7, 1, 1, 64, 64, 64, b.LEET_BF16, b.LEET_F32,
+                                    0, None) == b.LEET_ERR_INVALID_ARG
+

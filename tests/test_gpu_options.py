@@ -371,8 +371,9 @@ def test_rank_value_width_combinations_rejected(B):
     with pytest.raises(B.LeetAttnError) as ei:        # rank 64 with width 128 is not built
         B.leet_attn_forward_rd(qb, qb, vb, g)
     assert ei.value.status == B.LEET_ERR_UNSUPPORTED
-    # 8 segments: 7 boundary states per sequence, kept on half-segments (14 slots) of r x dv floats
-    assert B.workspace_bytes_rd(1, 32, 32768, 128, 256, B.LEET_BF16, 8) == 32 * 14 * 128 * 256 * 4
+    # 8 segments: 7 boundary states per sequence, kept on half-segments (14 slots) of r x dv floats,
+    # and one slot for the copy of the entering state
+    assert B.workspace_bytes_rd(1, 32, 32768, 128, 256, B.LEET_BF16, 8) == 32 * 15 * 128 * 256 * 4
     assert B.workspace_bytes_rd(1, 32, 32768, 64, 128, B.LEET_BF16, 8) == 0
 
 

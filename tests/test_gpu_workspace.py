@@ -1,0 +1,199 @@
+"""GPU tests of what surrounds the kernels: the state handed on in place, the library-owned
+workspace under growth and graph capture, and the per-call kernel and store-policy choices.
+All through the C ABI, against the fp64 oracle or against the library's own eager result."""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import elementwise_ok, max_rel_err
+from paper_2501_02573_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2501_02573_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(*ts):
+    return tuple(t.cuda() for t in ts)
+
+
+def check(got, ref, dtype, what):
+    err = max_rel_err(got, ref)
+    say(f"  {what}: max rel err {err:.3e} (tol {TOL[dtype]:.0e})")
+    assert np.isfinite(np.asarray(got)).all(), f"{what}: non-finite output"
+    assert err <= TOL[dtype], f"{what}: {err} > {TOL[dtype]}"
+    assert elementwise_ok(got, ref, TOL[dtype]), f"{what}: element-wise bound violated"
+
+
+# ---------------------------------------------------------------- state handed on in place
+IN_PLACE = [
+    # B, H, N, d, dtype, segments, kernel: grids larger than the device holds at once, a last segment of
+    # one chunk (57 chunks in 8 segments), so last segments can finish before first segments start
+    (2, 40, 57 * 64, 128, "bf16", 8, "wide"),          # 640 workgroups of the wide kernel
+    (1, 20, 57 * 64, 128, "bf16", 8, "column-split"),  # 640 workgroups of the column-split kernel
+    (2, 48, 57 * 64 - 30, 64, "bf16", 8, "auto"),
+    (1, 40, 29 * 64, 64, "f32", 8, "auto"),            # fp32: 29 chunks in segments of 4, a one-chunk tail
+]
+
+
+@pytest.mark.parametrize("case", IN_PLACE, ids=lambda c: "B%d_H%d_N%d_d%d_%s_seg%d_%s" % c)
+def test_state_in_aliased_to_state_out_with_segments(B, case):
+    """state_out may alias state_in: the walk must not read the caller's buffer after any workgroup
+    may have written it.  Run three times in place (prompt in pieces) and compare with the oracle's
+    three-piece continuation."""
+    Bn, H, N, d, dtype, segs, kernel = case
+    say(f"case in-place state {case}")
+    choice = {"wide": B.KERNEL_WIDE, "column-split": B.KERNEL_COLUMN_SPLIT, "auto": B.KERNEL_AUTO}[kernel]
+    code = B.LEET_F32 if dtype == "f32" else B.LEET_BF16
+    nseg, _ = B.query_plan_v3(Bn, H, N, d, d, code, segs, choice)
+    assert nseg == segs
+    pieces = 3
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, pieces * N, d, dtype, seed=4100 + d + H,
+                                                  gamma=W.make_gamma("pow2:3:9", H))
+    rng = np.random.default_rng(H)
+    s0 = torch.from_numpy((rng.standard_normal((Bn, H, d, d)) * 0.02).astype(np.float32))
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    S = s0.cuda()
+    outs = []
+    for i in range(pieces):
+        sl = slice(i * N, (i + 1) * N)
+        outs.append(B.leet_attn_forward_v3(dq[:, :, sl].contiguous(), dk[:, :, sl].contiguous(),
+                                           dv[:, :, sl].contiguous(), dg, state_in=S, state_out=S,
+                                           segments=segs, kernel=choice).cpu().numpy())
+    torch.cuda.synchronize()
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s0))
+    check(np.concatenate(outs, axis=2), ref, dtype, "three pieces, state in place: out")
+    check(S.cpu().numpy(), s_ref, dtype, "state after the third piece")
+
+
+# ---------------------------------------------------------------- library-owned workspace
+def test_library_workspace_growth_keeps_a_captured_graph_valid(B):
+    """A graph captured with the library-owned workspace keeps that block's address.  A later eager
+    call that needs a larger workspace must not free it: the replay after it equals the eager result."""
+    B.release_workspace()
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 4, 1100, 128, "bf16", 19)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    eager = B.leet_attn_forward_ex(dq, dk, dv, dg, segments=3).clone()   # sizes the workspace: 4 x 3 states
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.leet_attn_forward_ex(dq, dk, dv, dg, out=out, segments=3)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)
+
+    # a much larger call: the library workspace grows (32 sequences x 8 segments)
+    qb, kb, vb, gb = W.make_custom_forward_inputs(1, 32, 4096, 128, "bf16", 20)
+    big = B.leet_attn_forward_ex(*dev(qb, kb, vb, gb), segments=8)
+    torch.cuda.synchronize()
+    ref_big, _ = oracle.recurrent(*(W.to_f64(t) for t in (qb, kb, vb, gb)))
+    check(big.cpu().numpy(), ref_big, "bf16", "larger eager call after the capture")
+    # fill what a freed block could have been handed to
+    junk = [torch.full((1 << 20,), float("nan"), device="cuda") for _ in range(8)]
+    for rep in range(3):
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} after the workspace grew differs from eager"
+        B.leet_attn_forward_ex(*dev(qb, kb, vb, gb), segments=8)   # eager work between replays
+    del junk
+    del graph
+    B.release_workspace()
+
+
+def test_capture_refuses_to_allocate_the_library_workspace(B):
+    """Under stream capture the library does not allocate: with no (or too small a) workspace of its
+    own the call returns LEET_ERR_CAPTURE, records nothing, and leaves the capture usable."""
+    B.release_workspace()
+    q, k, v, gamma = W.make_custom_forward_inputs(1, 4, 1100, 128, "bf16", 21)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    need = B.workspace_bytes(1, 4, 1100, 128, B.LEET_BF16, 3)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    out = torch.full((1, 4, 1100, 128), 7.0, device="cuda")
+    out_ws = torch.zeros_like(out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        with pytest.raises(B.LeetAttnError) as ei:
+            B.leet_attn_forward_ex(dq, dk, dv, dg, out=out, segments=3)
+        # a caller-owned workspace is the way to capture without an eager call first
+        B.leet_attn_forward_ex(dq, dk, dv, dg, out=out_ws, workspace=ws, segments=3)
+    assert ei.value.status == B.LEET_ERR_CAPTURE
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0), "the refused call wrote to its output"
+    ref, _ = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    check(out_ws.cpu().numpy(), ref, "bf16", "captured call with a caller workspace")
+    # one segment needs no workspace at all: captures without anything sized beforehand
+    out1 = torch.zeros_like(out)
+    g1 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g1):
+        B.leet_attn_forward_ex(dq, dk, dv, dg, out=out1, segments=1)
+    g1.replay()
+    torch.cuda.synchronize()
+    check(out1.cpu().numpy(), ref, "bf16", "captured single-segment call")
+
+
+# ---------------------------------------------------------------- choices per call
+def test_kernel_choice_per_call(B):
+    """leet_attn_forward_v3 takes the kernel per call: both kernels, sized by the matching workspace
+    query, whatever the process-wide default says at that moment."""
+    Bn, H, N, d = 1, 6, 3000, 128
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=88, gamma=W.make_gamma("pow2:3:10", H))
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)))
+    try:
+        for default in (B.KERNEL_COLUMN_SPLIT, B.KERNEL_WIDE):
+            B.set_bf16_kernel(default)
+            for choice in (B.KERNEL_WIDE, B.KERNEL_COLUMN_SPLIT, B.KERNEL_AUTO):
+                nseg, kern = B.query_plan_v3(Bn, H, N, d, d, B.LEET_BF16, 0, choice)
+                if choice != B.KERNEL_AUTO:
+                    assert kern == choice
+                need = B.workspace_bytes_v3(Bn, H, N, d, d, B.LEET_BF16, 0, choice)
+                ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+                S = torch.empty(Bn, H, d, d, dtype=torch.float32, device="cuda")
+                say(f"case default={default} choice={choice} plan=({nseg}, {kern}) workspace={need}")
+                out = B.leet_attn_forward_v3(dq, dk, dv, dg, state_out=S, workspace=ws if need else None, kernel=choice)
+                check(out.cpu().numpy(), ref, "bf16", "out")
+                check(S.cpu().numpy(), s_ref, "bf16", "final state")
+    finally:
+        B.set_bf16_kernel(B.KERNEL_AUTO)
+
+
+def test_decode_store_policy_per_call(B):
+    """leet_attn_decode_step_v3 takes the store policy per call; the three policies give identical bits."""
+    cfg = W.DecodeConfig("t", 4, 6, 128, 5, 34, "pow2:1:9")
+    results = []
+    for store in (B.DECODE_STORE_CACHED, B.DECODE_STORE_STREAM, B.DECODE_STORE_AUTO, B.LEET_CHOICE_DEFAULT):
+        state0, gamma, steps = W.decode_stream(cfg)
+        S = state0.cuda(); dg = gamma.cuda()
+        outs = [B.leet_attn_decode_step_rd(*dev(q, k, v), dg, S, store=store).clone() for q, k, v in steps]
+        results.append((torch.stack(outs), S.clone()))
+    for o, s in results[1:]:
+        assert torch.equal(o, results[0][0]) and torch.equal(s, results[0][1])
+    state0, gamma, steps = W.decode_stream(cfg)
+    S_ref = W.to_f64(state0)
+    for n, (q, k, v) in enumerate(steps):
+        o_ref = oracle.decode_step(W.to_f64(q), W.to_f64(k), W.to_f64(v), W.to_f64(gamma), S_ref)
+        assert max_rel_err(results[0][0][n].cpu().numpy(), o_ref) < 1e-5
+    assert max_rel_err(results[0][1].cpu().numpy(), S_ref) < 1e-5
+    with pytest.raises(B.LeetAttnError):
+        B.leet_attn_decode_step_rd(*dev(q, k, v), dg, S, store=9)

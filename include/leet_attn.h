@@ -68,8 +68,10 @@ typedef enum {
     LEET_ERR_UNSUPPORTED = 2, /* d not in {64, 128}, unknown dtype or dtype combination, no gfx950 device */
     LEET_ERR_LAUNCH = 3,      /* the HIP runtime refused a launch or an allocation */
     LEET_ERR_TOO_LARGE = 4,   /* sizes overflow the library's index range */
-    LEET_ERR_CAPTURE = 5      /* `stream` is capturing and the library-owned workspace would have to be
+    LEET_ERR_CAPTURE = 5,     /* `stream` is capturing and the library-owned workspace would have to be
                                  allocated or grown; nothing was enqueued */
+    LEET_ERR_SCRATCH_LIMIT = 6 /* leet_attn_forward_static: the call's segment states exceed the static
+                                 scratch; nothing was enqueued */
 } leet_status;
 
 /*
@@ -146,6 +148,28 @@ int leet_attn_forward_v2(const void *q, const void *k, const void *v, const floa
                          void *workspace, size_t workspace_bytes, int segments,
                          int B, int H, int N, int d, int in_dtype, int out_dtype, int mask, void *stream);
 
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture that has not made
+ * an eager call first, tight serving loops, harnesses that forbid hipMalloc): leet_attn_forward_ex
+ * with the segment states in a fixed scratch array that is part of the library's device image
+ * (leet_attn_static_scratch_bytes() = 32 MiB, held by every GPU that loads the library until the
+ * process ends).  The call allocates and frees nothing; q, k, v, gamma, out and the states are
+ * the caller's as everywhere else.  Same kernels and same plan as leet_attn_forward_ex, hence
+ * bit-identical results.
+ *   segments   as for leet_attn_forward_ex.  If the plan's segment states need more than the
+ *              scratch holds (leet_attn_workspace_bytes tells), the status is
+ *              LEET_ERR_SCRATCH_LIMIT and nothing is enqueued; ask for fewer segments (one
+ *              segment needs no scratch at all) or use leet_attn_forward_ex.
+ *   dtype      LEET_F32 or LEET_BF16; fp32 output; decaying mask.
+ * All calls on one GPU share that GPU's scratch, which keeps the previous call's contents
+ * (nothing in it needs clearing: every slot a call reads is first written by that call's own
+ * kernels).  Calls that overlap on one GPU -- different streams, or a graph replay beside an
+ * eager call -- race on it; serialise them.
+ */
+int leet_attn_forward_static(const void *q, const void *k, const void *v, const float *gamma, float *out,
+                             const float *state_in, float *state_out, int segments,
+                             int B, int H, int N, int d, int dtype, void *stream);
+size_t leet_attn_static_scratch_bytes(void);
 
 /*
  * Row-based prefill: the same operator evaluated token by token as Alg. 1 (Appendix B.1) states

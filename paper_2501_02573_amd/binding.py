@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libleet_attn.so")
 LEET_F32, LEET_BF16, LEET_F16 = 0, 1, 2
 LEET_MASK_DECAY, LEET_MASK_CAUSAL = 0, 1
 LEET_OK, LEET_ERR_INVALID_ARG, LEET_ERR_UNSUPPORTED, LEET_ERR_LAUNCH, LEET_ERR_TOO_LARGE = 0, 1, 2, 3, 4
-LEET_ERR_CAPTURE = 5
+LEET_ERR_CAPTURE, LEET_ERR_SCRATCH_LIMIT = 5, 6
 LEET_CHOICE_DEFAULT = -1
 
 EXPORTED_SYMBOLS = (
@@ -40,6 +40,8 @@ EXPORTED_SYMBOLS = (
     "leet_attn_workspace_bytes_v3",
     "leet_attn_query_plan_v3",
     "leet_attn_decode_step_v3",
+    "leet_attn_forward_static",
+    "leet_attn_static_scratch_bytes",
     "leet_attn_forward_profile",
     "leet_attn_calibration_stream",
     "leet_attn_set_bf16_kernel",
@@ -96,6 +98,10 @@ def _load() -> ctypes.CDLL:
     lib.leet_attn_query_plan_v3.restype = i
     lib.leet_attn_decode_step_v3.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.leet_attn_decode_step_v3.restype = i
+    lib.leet_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+    lib.leet_attn_forward_static.restype = i
+    lib.leet_attn_static_scratch_bytes.argtypes = []
+    lib.leet_attn_static_scratch_bytes.restype = sz
     lib.leet_attn_forward_profile.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, vp,
                                               ctypes.POINTER(ctypes.c_float)]
     lib.leet_attn_forward_profile.restype = i
@@ -512,6 +518,29 @@ def query_plan_v3(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments:
     if st != LEET_OK:
         raise LeetAttnError(st, "leet_attn_query_plan_v3")
     return nseg.value, kern.value
+
+
+def static_scratch_bytes() -> int:
+    return int(lib.leet_attn_static_scratch_bytes())
+
+
+def leet_attn_forward_static(q, k, v, gamma, out: torch.Tensor, state_in: Optional[torch.Tensor] = None,
+                             state_out: Optional[torch.Tensor] = None, segments: int = 0) -> torch.Tensor:
+    """Chunked prefill that allocates nothing: segment states in the library's static scratch.
+
+    ``out`` is required (this binding allocates nothing for the call either)."""
+    B, H, N, d = _check_forward(q, k, v, gamma, out)
+    for name, s in (("state_in", state_in), ("state_out", state_out)):
+        if s is not None and (s.dtype != torch.float32 or tuple(s.shape) != (B, H, d, d)):
+            raise ValueError(f"{name} must be float32 [B, H, d, d]")
+    dev = _check_dev(q, k, v, gamma, out, state_in, state_out)
+    with torch.cuda.device(dev):
+        st = lib.leet_attn_forward_static(_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in),
+                                          _ptr(state_out), int(segments), B, H, N, d, _dtype_code(q),
+                                          ctypes.c_void_p(_stream_ptr(dev)))
+    if st != LEET_OK:
+        raise LeetAttnError(st, "leet_attn_forward_static")
+    return out
 
 
 def leet_attn_forward_recurrent_rd(q, k, v, gamma: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,

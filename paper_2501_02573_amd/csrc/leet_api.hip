@@ -233,6 +233,14 @@ size_t g_ws_size[kMaxDevices] = {0};
 std::vector<void*> g_ws_retired[kMaxDevices];
 int g_arch_ok[kMaxDevices] = {0};  // 0 unknown, 1 gfx950, -1 other
 
+// Scratch of the entry point that allocates nothing: segment boundary states, in device memory
+// that exists from the moment the library is loaded (every device that loads it holds its own copy
+// until the process ends).  The array's name is a host-side handle only; the device address of
+// each device's copy is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
 int current_device(int* dev) {
     if (hipGetDevice(dev) != hipSuccess) return LEET_ERR_LAUNCH;
     if (*dev < 0 || *dev >= kMaxDevices) return LEET_ERR_UNSUPPORTED;
@@ -243,6 +251,21 @@ int current_device(int* dev) {
         g_arch_ok[*dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : -1;
     }
     return g_arch_ok[*dev] == 1 ? LEET_OK : LEET_ERR_UNSUPPORTED;
+}
+
+// Device address of this device's copy of the static scratch (device `dev` is current).
+int static_scratch(int dev, void** out) {
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return LEET_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LEET_OK;
 }
 
 int own_workspace(int dev, size_t bytes, hipStream_t stream, void** out) {
@@ -277,10 +300,13 @@ int own_workspace(int dev, size_t bytes, hipStream_t stream, void** out) {
     return LEET_OK;
 }
 
+enum WorkspaceKind { kWsCallerOrOwned = 0, kWsStatic = 1 };
+
 int forward_impl(const void* q, const void* k, const void* v, const float* gamma, void* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
                  int segments, int B, int H, int N, int d, int dv, int dtype, int out_dtype, int mask,
-                 void* stream, float* kernel_ms, int kernel_choice = LEET_CHOICE_DEFAULT) {
+                 void* stream, float* kernel_ms, int kernel_choice = LEET_CHOICE_DEFAULT,
+                 WorkspaceKind ws_kind = kWsCallerOrOwned) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     if (kernel_choice != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel_choice)) return LEET_ERR_INVALID_ARG;
     const bool no_decay = mask == LEET_MASK_CAUSAL;
@@ -300,6 +326,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
 
     Plan plan;
     if (!make_plan(BH, N, d, dv, dtype, segments, kernel_choice, &plan)) return LEET_ERR_TOO_LARGE;
+    if (ws_kind == kWsStatic && plan.ws_bytes > kStaticScratchBytes) return LEET_ERR_SCRATCH_LIMIT;
     // the timing aid relaunches the walk: with the state handed on in place, later launches would
     // start from the state the first one left
     if (kernel_ms && state_in && state_in == state_out) return LEET_ERR_INVALID_ARG;
@@ -310,7 +337,10 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
 
     void* ws = nullptr;
     if (plan.nseg > 1) {
-        if (workspace) {
+        if (ws_kind == kWsStatic) {
+            status = static_scratch(dev, &ws);
+            if (status != LEET_OK) return status;
+        } else if (workspace) {
             if (workspace_bytes < plan.ws_bytes) return LEET_ERR_INVALID_ARG;
             ws = workspace;
         } else {
@@ -481,6 +511,16 @@ int leet_attn_forward_v3(const void* q, const void* k, const void* v, const floa
                         B, H, N, r, dv, in_dtype, out_dtype, mask, stream, nullptr, kernel);
 }
 
+int leet_attn_forward_static(const void* q, const void* k, const void* v, const float* gamma, float* out,
+                             const float* state_in, float* state_out, int segments,
+                             int B, int H, int N, int d, int dtype, void* stream) {
+    if (dtype == LEET_F16) return LEET_ERR_UNSUPPORTED;
+    return forward_impl(q, k, v, gamma, out, state_in, state_out, nullptr, 0, segments, B, H, N, d, d, dtype,
+                        LEET_F32, LEET_MASK_DECAY, stream, nullptr, LEET_CHOICE_DEFAULT, kWsStatic);
+}
+
+size_t leet_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
 size_t leet_attn_workspace_bytes_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel) {
     int status = LEET_OK;
     if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
@@ -620,6 +660,7 @@ const char* leet_attn_strerror(int status) {
         case LEET_ERR_LAUNCH: return "HIP runtime error (launch or allocation failed)";
         case LEET_ERR_TOO_LARGE: return "sizes exceed the library's index range";
         case LEET_ERR_CAPTURE: return "the library-owned workspace would have to be allocated or grown while the stream is capturing (make one eager call of this size first, or pass a caller-owned workspace)";
+        case LEET_ERR_SCRATCH_LIMIT: return "the segment states of this call exceed the static scratch of leet_attn_forward_static (32 MiB; request fewer segments, or use leet_attn_forward_ex with a workspace)";
         default: return "unknown status";
     }
 }

@@ -50,7 +50,7 @@ def test_library_exports_every_declared_symbol(lib):
 def test_strerror_and_version(lib):
     from paper_2501_02573_amd import binding
     assert binding.strerror(0) == "ok"
-    for st in (1, 2, 3, 4, 5, 99):
+    for st in (1, 2, 3, 4, 5, 6, 99):
         assert len(binding.strerror(st)) > 0
     assert re.fullmatch(r"\d+\.\d+\.\d+", binding.version())
 
@@ -266,3 +266,21 @@ def test_per_call_choices_match_the_setters(lib):
     assert lib.leet_attn_forward_v3(p, p, p, p, p, None, None, None, 0, 0, 7, 1, 1, 64, 64, 64, b.LEET_BF16, b.LEET_F32,
                                     0, None) == b.LEET_ERR_INVALID_ARG
 
+
+def test_static_scratch_entry_point_limits(lib):
+    """The entry point that allocates nothing refuses, on the host, plans whose segment states exceed
+    its static scratch, and takes the same argument checks as leet_attn_forward_ex."""
+    from paper_2501_02573_amd import binding as b
+    cap = b.static_scratch_bytes()
+    assert cap == 32 << 20
+    p = ctypes.c_void_p(0x1000)
+    st = lib.leet_attn_forward_static
+    # the long-context benchmark shape fits under the library's own plan
+    assert 0 < b.workspace_bytes(1, 32, 32768, 128, b.LEET_BF16) <= cap
+    # 64 sequences cut into 16 segments: 64 * 16 states of 64 KiB = 64 MiB
+    assert b.workspace_bytes(4, 16, 8192, 128, b.LEET_BF16, 16) > cap
+    assert st(p, p, p, p, p, None, None, 16, 4, 16, 8192, 128, b.LEET_BF16, None) == b.LEET_ERR_SCRATCH_LIMIT
+    assert st(None, p, p, p, p, None, None, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
+    assert st(p, p, p, p, p, None, None, 0, 1, 1, 64, 96, b.LEET_F32, None) == b.LEET_ERR_UNSUPPORTED
+    assert st(p, p, p, p, p, None, None, 0, 1, 1, 64, 64, b.LEET_F16, None) == b.LEET_ERR_UNSUPPORTED
+    assert "32 MiB" in b.strerror(b.LEET_ERR_SCRATCH_LIMIT)

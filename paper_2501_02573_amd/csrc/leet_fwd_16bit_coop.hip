@@ -126,14 +126,10 @@ __device__ __forceinline__ f32x16 zero16() {
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
 // E: ElemBf16 or ElemF16 (input type).  kOut16: outputs in the input type instead of fp32.
-#ifndef LEET_COOP_LW
-#define LEET_COOP_LW 2
-#endif
-#ifndef LEET_COOP_NS
-#define LEET_COOP_NS 2
-#endif
-constexpr int kCoopLoaderWaves = LEET_COOP_LW;
-constexpr int kCoopStages = LEET_COOP_NS;
+// Two loader waves with two register stages each: more of either measured no faster (four waves,
+// three stages), the loads are bound by what one compute unit keeps in flight, not by issue.
+constexpr int kCoopLoaderWaves = 2;
+constexpr int kCoopStages = 2;
 constexpr int kCoopThreads = 384 + 64 * kCoopLoaderWaves;
 
 // D: width of q and k rows (rank); DV: width of v and out rows (DV / 32 slices per sequence).
@@ -243,20 +239,23 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     auto prefetch = [&](Stage& st, int c) {
         c = min(c, n - 1);
         const int shift = (c == n - 1) ? last_shift : 0;
-        const size_t tok0 = (size_t)(tok_begin + c * kChunk - shift);  // wave-uniform
+        // Base = the chunk's first token (tile row `shift`), offsets count rows from there: every
+        // address formed lies inside the sequence, also for a ragged first chunk (N < 64), whose
+        // tile begins before token 0.
+        const size_t tok0 = (size_t)(tok_begin + c * kChunk);  // wave-uniform
         const uint16_t* qc = qg + tok0 * D;
         const uint16_t* kc = kg + tok0 * D;
         const uint16_t* vc = vg + tok0 * DV;
 #pragma unroll
         for (int m = 0; m < QPL; ++m) {
-            const int row = max(qk_row + m * RPL, shift);
+            const int row = max(qk_row + m * RPL - shift, 0);
             const unsigned off = (unsigned)(row * D + qk_cc * 8);
             if (kOut) st.q[m] = *reinterpret_cast<const u32x4*>(qc + off);
             st.k[m] = *reinterpret_cast<const u32x4*>(kc + off);
         }
 #pragma unroll
         for (int m = 0; m < VPL; ++m)
-            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m, shift) * DV + c0 + v_cc * 8));
+            st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m - shift, 0) * DV + c0 + v_cc * 8));
     };
 
     __syncthreads();  // tables, S^T(0) visible
@@ -450,7 +449,8 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     auto store_chunk = [&](int t) {
         const int c = t - 2;
         const int cshift = (c == n - 1) ? last_shift : 0;
-        const size_t tile_off = (size_t)(tok_begin + c * kChunk - cshift) * DV + c0;  // + row * DV
+        // offset of the chunk's first token (tile row cshift); rows are counted from there
+        const size_t tile_off = (size_t)(tok_begin + c * kChunk) * DV + c0;
         if (!kOut16) {
             // 128-byte row pieces: lane -> (row l/8 of eight rows, 16 bytes l%8)
             float* oc = og + tile_off + 4 * (l & 7);
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             for (int m = 0; m < 8; ++m) {
                 const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
                 const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)row * DV));
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)(row - cshift) * DV));
             }
         } else {
             // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
@@ -472,7 +472,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
                 const f32x4 a = *reinterpret_cast<const f32x4*>(src);
                 const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
                 const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)row * DV));
+                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)(row - cshift) * DV));
             }
         }
     };
@@ -544,7 +544,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             __syncthreads();
             __syncthreads();  // iteration n + 1: the store wave's last chunk
         } else {
-            // wave 5 (state tile 3 where it exists, and the stores), and in the pre-pass every state wave
+            // wave 5 (the stores of the walk), and in the pre-pass every wave that owns a state tile
             for (int t = 0; t <= t_end; ++t) {
                 if (state_wave && t < n) score_state(t, no, yes);
                 if (store_wave && t >= 2) store_chunk(t);

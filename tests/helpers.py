@@ -31,6 +31,27 @@ def elementwise_ok(got, ref, tol):
     return bool(np.all(np.abs(g - r) <= tol * (np.abs(r) + rms) + 1e-300))
 
 
+def elementwise_ok_windowed(got, ref, tol, window=64):
+    """The element-wise bound with the rms taken over the window of `window` tokens that the element
+    sits in (per (b,h)), for [B,H,N,d] arrays: |got-ref| <= tol * (|ref| + rms_window(ref)).
+
+    The rounding errors of the 16-bit kernels scale with the operands of the moment -- the state is
+    rounded to the input type once per 64-token chunk -- so where the output scale changes along the
+    sequence (a large entering state on a fast-decaying head) the scale that an error must be held
+    against is the local one, not the rms of the whole head.  Tighter than the per-head bound where
+    the outputs are small, looser where they are large."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    B, H, N, d = ref.shape
+    ok = True
+    for t0 in range(0, N, window):
+        r = ref[:, :, t0:t0 + window].reshape(B, H, -1)
+        g = got[:, :, t0:t0 + window].reshape(B, H, -1)
+        rms = np.sqrt((r * r).mean(axis=2, keepdims=True))
+        ok = ok and bool(np.all(np.abs(g - r) <= tol * (np.abs(r) + rms) + 1e-300))
+    return ok
+
+
 def parse_golden(path):
     """'name a b ; c d' lines -> dict name -> 2-D float array (1-D rows for single-row entries)."""
     out = {}

@@ -6,27 +6,42 @@ outputs, store, state update; one column-split chunk-walk kernel where the libra
 choice takes it (the headline shape), else segment pre-pass, segment scan and chunk walk -- over one batch
 of the headline workload: B=4, H=16, N=4096, d=128, bf16 inputs, fp32 accumulate and output,
 per-head gamma_h = 1 - 2^-(5 + 3h/15), seeded synthetic q, k, v ~ N(0,1)/sqrt(d).  Inputs
-are resident in HBM before the timed region.  The decode step (config 5) and the
-long-context prefill (config 4) are timed in the same run and reported under "extra".
+are resident in HBM before the timed region.
 
 Prints ONE JSON line.  ``value`` is tokens/s (B*N per step) of the headline workload over
-exactly --steps steps of plain library calls; ``ms_per_step_graph`` is the same step captured
-once into a HIP graph and replayed (reported for comparison, it measured no faster).
-``roofline`` is for the dominant kernel (the chunk walk), whose per-launch duration is measured
-with HIP events on the launch stream; ``cpu_baseline`` is the fp64 oracle (recurrent form)
-timed on this host's cores on the same workload.
+exactly --steps steps of plain library calls after --warmup untimed ones.  Beside it:
 
-The device's clocks take on the order of 100 ms of continuous work to settle (kernel durations in
-a profiler trace fall steadily over the first several hundred launches), so short runs from an
-idle device read 10-25 % slower.  Two things keep that out of the figures: before each timed
-section the device is kept busy for --settle-ms (default 250 ms) with a plain copy kernel on
-buffers of its own -- conditioning, not workload, and outside every timed region -- and the
-defaults are long (1000 warm-up and 1000 timed steps).
+``stats``            the timing protocol of the paper's single-layer tables (Section 5.1: 15
+                     repetitions, mean and standard deviation), with the minimum: 15 further timed
+                     sections of the same step, each bracketed by synchronisation
+``no_settle``        the same K steps without the conditioning described below
+``cold_inputs``      the same step over three input sets in rotation (603 MB of q, k, v: more than
+                     the 256 MB last-level cache holds), so every step's inputs come from HBM
+``roofline``         the dominant kernel (the chunk walk) against the HBM roofline, its per-launch
+                     duration from HIP events on the launch stream over the timed region
+``extra``            the other workloads, each with its own fixed, settled step counts (independent
+                     of --steps): long context (config 4), decode (config 5, resident and with
+                     three states in rotation under each store policy), the fp32 kernel (config 2
+                     and the headline shape in fp32), the two element-wise comparison kernels
+``cpu_baseline``     the fp64 oracle timed on this host's cores (recurrent form with all threads
+                     and with one; the quadratic form on configs 1-2 and on sampled rows of config 3)
+
+Conditioning.  When a kernel of this library starts on an idle device, or right after a
+different kind of kernel, its launches first get slower for some tens of milliseconds and then
+settle (headline step from idle: 81 us for twenty launches, 96-110 us for the next hundreds,
+70 us from then on; after 250 ms of a plain copy kernel: 78 us, then 86-90 us, then 70 us): the
+device's power management reacts to the change of load.  A short timed section therefore reads
+10-50 % slower than the rate a busy server sees.  Before each timed section the device is kept
+busy for --settle-ms (default 500 ms) with the same kind of work -- the leg's own kernel, for the
+headline on a second set of buffers of the same shape, so that the --warmup steps that follow are
+still the first to touch the timed buffers.  That is conditioning, not workload, and outside every
+timed region; ``no_settle`` is the headline figure without it.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -35,9 +50,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+MFMA_FP32_PEAK_TFLOPS = 157.3    # MI355X fp32 MFMA, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector ALUs, published (256 CUs x 4 SIMDs x 2.4 GHz x 64 flop/clk with packed fp32)
+
+REPS = 15                        # repetitions of the timing protocol (Section 5.1)
 
 
 def parse_args():
@@ -45,11 +63,11 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=1000)
-    ap.add_argument("--settle-ms", type=float, default=250.0,
-                    help="keep the device busy this long with a plain copy kernel before each timed section, "
+    ap.add_argument("--settle-ms", type=float, default=500.0,
+                    help="keep the device busy this long with the leg's own kernel before each timed section, "
                          "so that its clocks have settled whatever --warmup is (0 disables)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the config-4 and decode legs")
+    ap.add_argument("--no-extra", action="store_true", help="skip every leg but the headline")
     ap.add_argument("--no-graph", action="store_true", help="time plain calls only (no HIP graph replay)")
     ap.add_argument("--segments", type=int, default=0, help="0 = library's choice (the shipped configuration)")
     ap.add_argument("--kernel", choices=["auto", "wide", "column-split"], default="auto",
@@ -69,24 +87,26 @@ def alg_flops_forward(cfg):
     return cfg.B * cfg.H * cfg.N * (4 * cfg.d * cfg.d + 2 * 64 * cfg.d)
 
 
-_SETTLE = {"ms": 0.0, "fn": None}
+_SETTLE = {"ms": 0.0}
 
 
-def settle(torch):
-    """Device conditioning, outside every timed region and not part of the workload: a plain copy
-    kernel (64 MiB buffers, not the workload's) keeps the GPU busy until its clocks have settled."""
-    if _SETTLE["ms"] <= 0 or _SETTLE["fn"] is None:
+def settle(torch, fn, ms=None):
+    """Device conditioning, outside every timed region and not part of the workload: `fn` (a launch
+    of the same kind of kernel as the timed one) keeps the GPU busy until its clocks have settled."""
+    ms = _SETTLE["ms"] if ms is None else ms
+    if ms <= 0 or fn is None:
         return
     t0 = time.perf_counter()
-    while (time.perf_counter() - t0) * 1e3 < _SETTLE["ms"]:
-        for _ in range(50):
-            _SETTLE["fn"]()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(20):
+            fn()
         torch.cuda.synchronize()
 
 
-def time_eager(torch, step, steps, warmup):
-    """(host-clock ms per step, HIP-event ms per step) over exactly `steps` plain calls."""
-    settle(torch)
+def time_eager(torch, step, steps, warmup, cond=None):
+    """(host-clock ms per step, HIP-event ms per step) over exactly `steps` plain calls, after
+    conditioning with `cond` (None: none) and exactly `warmup` untimed calls."""
+    settle(torch, cond)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -100,7 +120,28 @@ def time_eager(torch, step, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
-def time_graph(torch, step, steps, warmup):
+def time_reps(torch, step, steps, warmup, reps=REPS, cond=None):
+    """The paper's protocol: `reps` timed sections of `steps` steps each (one conditioning and one
+    warm-up before the first); mean, standard deviation and minimum of the per-step time, ms."""
+    settle(torch, cond)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    samples = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        samples.append(e0.elapsed_time(e1) / steps)
+    mean = sum(samples) / len(samples)
+    std = math.sqrt(sum((x - mean) ** 2 for x in samples) / (len(samples) - 1)) if len(samples) > 1 else 0.0
+    return {"reps": reps, "steps_per_rep": steps, "warmup": warmup, "mean_ms": mean, "std_ms": std, "min_ms": min(samples)}
+
+
+def time_graph(torch, step, steps, warmup, cond=None):
     """One step captured into a HIP graph, replayed `steps` times; None if capture fails."""
     try:
         side = torch.cuda.Stream()
@@ -113,7 +154,7 @@ def time_graph(torch, step, steps, warmup):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        settle(torch)
+        settle(torch, cond)
         for _ in range(warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -135,30 +176,44 @@ def kernel_times(binding, q, k, v, gamma, out, reps, segments):
     return [a / reps for a in acc]
 
 
-def load_traffic(workload, kernel):
-    """HBM bytes per launch of the dominant kernel from the committed profiler summary, or None."""
+def load_traffic(binding, workload, kernel):
+    """HBM bytes per launch of a kernel from the committed profiler summary -- measured by
+    rocprofv3 PMC runs, not in this run -- or None when that summary was taken from another
+    version of the library than the one loaded now."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             rec = json.load(f)
+        if rec.get("_library_version") != binding.version():
+            return None
         ent = rec.get(f"{workload}/{kernel}")
         return None if ent is None else ent.get("hbm_bytes_per_launch")
     except (OSError, ValueError):
         return None
 
 
-def prefill_leg(torch, binding, W, cfg, dev, steps, warmup, segments, use_graph):
+def prefill_leg(torch, binding, W, cfg, dev, steps, warmup, segments, use_graph, rep_steps, rep_warmup, second_set):
+    """One prefill workload: K timed steps, the 15-repetition protocol, graph replay, per-kernel times.
+    second_set: condition the device on a copy of the buffers (the headline, whose --warmup steps are
+    then the first to touch the timed buffers) instead of on the timed buffers themselves."""
     q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
     out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
 
     def step():
         binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
 
-    ms_eager, ms_events = time_eager(torch, step, steps, warmup)
-    ms_graph = time_graph(torch, step, steps, warmup) if use_graph else None
+    cond = step
+    if second_set:
+        q2, k2, v2, out2 = (torch.empty_like(t).copy_(t) for t in (q, k, v, out))
+
+        def cond():
+            binding.leet_attn_forward_ex(q2, k2, v2, gamma, out=out2, segments=segments)
+
+    ms_eager, ms_events = time_eager(torch, step, steps, warmup, cond)
+    stats = time_reps(torch, step, rep_steps, rep_warmup, cond=cond)
+    ms_graph = time_graph(torch, step, steps, warmup, cond) if use_graph else None
     kms = kernel_times(binding, q, k, v, gamma, out, max(3, min(steps, 20)), segments)
-    del q, k, v, out
-    return ms_eager, ms_graph, kms, ms_events
+    return {"ms": ms_eager, "ms_events": ms_events, "stats": stats, "ms_graph": ms_graph, "kernel_ms": kms}
 
 
 def main():
@@ -180,28 +235,48 @@ def main():
                              "column-split": binding.KERNEL_COLUMN_SPLIT}[args.kernel])
 
     _SETTLE["ms"] = args.settle_ms
-    if args.settle_ms > 0:
-        sa = torch.zeros(16 << 20, dtype=torch.float32, device=dev)
-        sb = torch.empty_like(sa)
-        _SETTLE["fn"] = lambda: binding.calibration_stream("copy", sa, sb, sa.numel() * 4, 4096)
 
     # ---------------- headline: config 3
     cfg = W.CONFIG3
     nseg3, kern3 = binding.query_plan(cfg.B, cfg.H, cfg.N, cfg.d, binding.LEET_BF16, args.segments)
     kernel_ran = "column-split" if kern3 == binding.KERNEL_COLUMN_SPLIT else "wide"
     walk_name = {"wide": "fwd_16bit_kernel<128,128,true,bf16>", "column-split": "fwd_16bit_coop_kernel<128,128,true,bf16>"}[kernel_ran]
-    ms_eager, ms_graph, kms, ms_events = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup,
-                                                     args.segments, not args.no_graph)
-    ms = ms_eager
+    rep_steps = max(20, min(args.steps, 200))
+    leg = prefill_leg(torch, binding, W, cfg, dev, args.steps, args.warmup, args.segments, not args.no_graph,
+                      rep_steps, max(args.warmup, 100), second_set=True)
+    ms, ms_events, kms = leg["ms"], leg["ms_events"], leg["kernel_ms"]
     tokens = cfg.B * cfg.N
     nbytes = alg_bytes_forward(cfg, 2)
     nflops = alg_flops_forward(cfg)
+
+    # the same K steps from an idle device, without the conditioning
+    q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
+    out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    time.sleep(1.0)
+    ms_cold_clock, _ = time_eager(torch, lambda: binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=args.segments),
+                                  args.steps, args.warmup, cond=None)
+    # three input sets in rotation: 603 MB of q, k, v, so that no step finds its inputs in the 256 MB
+    # last-level cache (the plain loop re-reads the same 201 MB every step)
+    sets = [(q, k, v, out)] + [tuple(torch.empty_like(t).copy_(t) for t in (q, k, v, out)) for _ in range(2)]
+    turn = [0]
+
+    def rotating_step():
+        a, b, c, o = sets[turn[0] % 3]
+        turn[0] += 1
+        binding.leet_attn_forward_ex(a, b, c, gamma, out=o, segments=args.segments)
+
+    cold_stats = time_reps(torch, rotating_step, 60, 120, cond=rotating_step)
+    del sets, q, k, v, out
+
     # Duration of the dominant kernel.  With one segment the step is that one kernel, and the HIP
     # events around the timed steps give its average launch-to-launch time in the timed region
     # itself (an upper bound on its duration).  With segments the step is three kernels and the
     # walk's share comes from events around repeated launches of it, taken after the timed loops.
     single_kernel = nseg3 == 1
     walk_ms = ms_events if single_kernel else kms[2]
+    hbm_frac = nbytes / (walk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    mfma_frac = nflops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
     result = {
         "metric": "tokens/s, chunked decayed causal linear attention forward (B4 H16 N4096 d128 bf16)",
         "value": tokens / (ms * 1e-3),
@@ -210,6 +285,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "settle_ms": args.settle_ms,
+        "settle": "before the --warmup steps the device runs the same kernel on a second set of buffers for settle_ms "
+                  "(conditioning, untimed; see no_settle for the figure without it)",
         "ms_per_step": ms,
         "higher_is_better": True,
         "scaling": "weak",
@@ -220,9 +297,14 @@ def main():
                    "chunk": 64, "segments": nseg3, "kernel": kernel_ran, "kernel_choice": args.kernel,
                    "launch": "eager",
                    "gamma": "1-2^-(5+3h/15)", "seed": cfg.seed, "out_dtype": "f32"},
-        "ms_per_step_graph": ms_graph,
+        "stats": dict(leg["stats"], protocol="15 timed sections after one warm-up, HIP events, ms per step"),
+        "no_settle": {"ms_per_step": ms_cold_clock,
+                      "note": "the same --warmup and --steps after one idle second, without the conditioning"},
+        "cold_inputs": dict(cold_stats, hbm_frac_mean=nbytes / (cold_stats["mean_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            note="three sets of q, k, v, out in rotation (603 MB of inputs): no step finds its inputs in the last-level cache"),
+        "ms_per_step_graph": leg["ms_graph"],
         "tflops_algorithmic": nflops / (ms * 1e-3) / 1e12,
-        "mfma_peak_frac": nflops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "mfma_peak_frac": mfma_frac,
         "hbm_frac_whole_step": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": {"segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": walk_ms},
         "roofline": {
@@ -231,8 +313,9 @@ def main():
             "achieved": nbytes / (walk_ms * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": nbytes / (walk_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": load_traffic(cfg.name, kernel_ran),
+            "frac": hbm_frac,
+            "traffic": load_traffic(binding, cfg.name, kernel_ran),
+            "traffic_source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE and WRITE_SIZE runs of this library version; null if stale)",
             "algorithmic_bytes_per_launch": nbytes,
             "avg_launch_ms": walk_ms,
             "timed_by": ("HIP events around the timed steps (one kernel per step)" if single_kernel else
@@ -240,6 +323,11 @@ def main():
         },
         "kernel_ms_isolated": {"note": "event-timed repeated launches after the timed loops",
                                "segment_state_prepass": kms[0], "segment_scan": kms[1], "chunk_walk": kms[2]},
+        "targets": {
+            "mfma_peak_frac_asked": 0.5, "mfma_peak_frac": mfma_frac, "met": bool(mfma_frac >= 0.5),
+            "note": "1280 B of compulsory traffic per 81920 flops put the HBM roofline at 0.20 of the bf16 MFMA "
+                    "peak for this operator with fp32 output; HBM is the binding roof (roofline.frac)",
+        },
     }
 
     if args.calibrate:
@@ -250,141 +338,209 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    # ---------------- extra legs: long context (config 4) and decode (config 5)
     if not args.no_extra:
-        extra = {}
-        cfg4 = W.CONFIG4
-        e4, g4, kms4, _ = prefill_leg(torch, binding, W, cfg4, dev, max(5, args.steps // 2), max(2, args.warmup // 2), 0,
-                                   not args.no_graph)
-        ms4 = e4
-        b4, f4 = alg_bytes_forward(cfg4, 2), alg_flops_forward(cfg4)
-        extra["long_context"] = {
-            "workload": cfg4.name, "ms_per_step": ms4, "ms_per_step_graph": g4,
-            "tokens_per_s": cfg4.B * cfg4.N / (ms4 * 1e-3),
-            "tflops_algorithmic": f4 / (ms4 * 1e-3) / 1e12,
-            "hbm_frac_whole_step": b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "kernel_ms": {"segment_state_prepass": kms4[0], "segment_scan": kms4[1], "chunk_walk": kms4[2]},
-            "walk_hbm_frac": b4 / (kms4[2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        }
+        result["extra"] = extra_legs(torch, binding, W, dev, cfg, tokens, not args.no_graph)
 
-        c5 = W.CONFIG5
-        state0, gamma5, steps_it = W.decode_stream(c5)
-        S = state0.to(dev)
-        gamma5 = gamma5.to(dev)
-        qkv = [tuple(t.to(dev) for t in next(steps_it)) for _ in range(4)]
-        o = torch.empty((c5.B, c5.H, c5.d), dtype=torch.float32, device=dev)
-        settle(torch)
-        for i in range(16):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, S, o)
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(c5.steps):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, S, o)
-        e1.record()
-        torch.cuda.synchronize()
-        ms5 = e0.elapsed_time(e1) / c5.steps
-        b5 = c5.B * c5.H * (2 * c5.d * c5.d * 4 + 3 * c5.d * 2 + c5.d * 4)
-        extra["decode"] = {
-            "workload": c5.name, "us_per_step": ms5 * 1e3, "tokens_per_s": c5.B / (ms5 * 1e-3),
-            "roofline": {"kernel": "decode_kernel<128,128,bf16>", "bound": "hbm",
-                         "achieved": b5 / (ms5 * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": b5 / (ms5 * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": load_traffic(c5.name, "decode"),
-                         "algorithmic_bytes_per_launch": b5,
-                         "note": "256 back-to-back steps; the 128 MiB state fits the 256 MB Infinity Cache"},
-        }
-        # the same step over three distinct 128 MiB state buffers in turn (384 MiB > the 256 MB
-        # Infinity Cache), so that every step streams its state from and to HBM
-        cold = [S, S.clone(), S.clone()]
-        for i in range(12):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, cold[i % 3], o)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(c5.steps):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, cold[i % 3], o)
-        e1.record()
-        torch.cuda.synchronize()
-        ms5c = e0.elapsed_time(e1) / c5.steps
-        binding.set_decode_store(binding.DECODE_STORE_STREAM)
-        for i in range(12):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, cold[i % 3], o)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(c5.steps):
-            binding.leet_attn_decode_step(*qkv[i % 4], gamma5, cold[i % 3], o)
-        e1.record()
-        torch.cuda.synchronize()
-        binding.set_decode_store(binding.DECODE_STORE_AUTO)
-        ms5s = e0.elapsed_time(e1) / c5.steps
-        extra["decode_cold"] = {
-            "workload": c5.name + ", three state buffers in rotation (every step streams from and to HBM)",
-            "default_store_policy": {"us_per_step": ms5c * 1e3, "achieved_GBps": b5 / (ms5c * 1e-3) / 1e9,
-                                     "hbm_frac": b5 / (ms5c * 1e-3) / 1e9 / HBM_PEAK_GBS},
-            "streaming_stores": {"us_per_step": ms5s * 1e3, "achieved_GBps": b5 / (ms5s * 1e-3) / 1e9,
-                                 "hbm_frac": b5 / (ms5s * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        }
-        del S, qkv, o, cold
-
-        # the two element-wise comparison kernels on the headline workload (vector ALUs only):
-        # 3 multiply-adds = 5 flops per (token, rank index, value column)
-        q3, k3, v3, g3 = (t.to(dev) for t in W.make_forward_inputs(cfg))
-        o3 = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
-        alu_flops = 5.0 * cfg.B * cfg.H * cfg.N * cfg.d * cfg.d
-        extra["elementwise_methods"] = {"workload": cfg.name, "flops_per_call": alu_flops}
-        for name, fn in (("row_based", binding.leet_attn_forward_recurrent), ("fleet_attention", binding.leet_attn_forward_fleet)):
-            settle(torch)
-            for _ in range(5):
-                fn(q3, k3, v3, g3, out=o3)
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(20):
-                fn(q3, k3, v3, g3, out=o3)
-            e1.record()
-            torch.cuda.synchronize()
-            ms_e = e0.elapsed_time(e1) / 20
-            extra["elementwise_methods"][name] = {
-                "ms_per_call": ms_e, "tokens_per_s": tokens / (ms_e * 1e-3),
-                "roofline": {"kernel": "elementwise_kernel<128,128,bf16,16,%s>" % ("rank-major" if name == "fleet_attention" else "token-major"),
-                             "bound": "alu", "achieved": alu_flops / (ms_e * 1e-3) / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS,
-                             "unit": "TFLOP/s", "frac": alu_flops / (ms_e * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, "traffic": None},
-            }
-        del q3, k3, v3, o3
-        result["extra"] = extra
-
-    # ---------------- CPU baseline: the oracle as it stands, on this host's cores
     if not args.no_cpu_baseline:
-        import oracle
-        qc, kc, vc, gc = W.make_forward_inputs(cfg)
-        q64, k64, v64, g64 = (W.to_f64(t) for t in (qc, kc, vc, gc))
-        best = None
-        for _ in range(3):
-            t0 = time.perf_counter()
-            oracle.recurrent(q64, k64, v64, g64)
-            dt = time.perf_counter() - t0
-            best = dt if best is None else min(best, dt)
-        result["cpu_baseline"] = {
-            "value": tokens / best, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"whole {cfg.name} workload, fp64 recurrent form (Alg. 1 with decay), best of 3, {best:.2f} s",
-        }
-        # the decode oracle on a bounded sample of config 5: 8 of its 256 steps
-        import numpy as np
-        c5 = W.CONFIG5
-        state0, g5, it5 = W.decode_stream(c5)
-        S64 = np.ascontiguousarray(W.to_f64(state0))
-        g5 = W.to_f64(g5)
-        sample = [tuple(W.to_f64(t) for t in next(it5)) for _ in range(8)]
-        t0 = time.perf_counter()
-        for q5, k5, v5 in sample:
-            oracle.decode_step(q5, k5, v5, g5, S64)
-        dt5 = time.perf_counter() - t0
-        result["cpu_baseline"]["decode"] = {
-            "value": c5.B * len(sample) / dt5, "unit": "tokens/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"8 of the 256 steps of {c5.name}, fp64 decode step, {dt5:.2f} s",
-        }
+        result["cpu_baseline"] = cpu_baseline(W, cfg, tokens)
 
     print(json.dumps(result))
+
+
+def extra_legs(torch, binding, W, dev, cfg3, tokens3, use_graph):
+    """The other workloads.  Step counts are fixed here (long enough to be settled, short enough to
+    cost a fraction of a second each) and do not depend on --steps."""
+    extra = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, warm, steps):
+        settle(torch, fn)
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    # ---- long context (config 4): 100 warm-up + 200 timed steps, then the 15-repetition protocol
+    cfg4 = W.CONFIG4
+    leg4 = prefill_leg(torch, binding, W, cfg4, dev, 200, 100, 0, use_graph, 40, 40, second_set=False)
+    ms4, kms4 = leg4["ms"], leg4["kernel_ms"]
+    b4, f4 = alg_bytes_forward(cfg4, 2), alg_flops_forward(cfg4)
+    nseg4, kern4 = binding.query_plan(cfg4.B, cfg4.H, cfg4.N, cfg4.d, binding.LEET_BF16)
+    extra["long_context"] = {
+        "workload": cfg4.name, "steps": 200, "warmup": 100, "ms_per_step": ms4, "ms_per_step_graph": leg4["ms_graph"],
+        "stats": leg4["stats"], "segments": nseg4, "kernel": "column-split" if kern4 == binding.KERNEL_COLUMN_SPLIT else "wide",
+        "tokens_per_s": cfg4.B * cfg4.N / (ms4 * 1e-3),
+        "tflops_algorithmic": f4 / (ms4 * 1e-3) / 1e12,
+        "hbm_frac_whole_step": b4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms": {"segment_state_prepass": kms4[0], "segment_scan": kms4[1], "chunk_walk": kms4[2]},
+        "walk_hbm_frac": b4 / (kms4[2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": {name: load_traffic(binding, cfg4.name, name) for name in ("prepass", "scan", "walk")},
+        "note": "805 MB of inputs: every step streams from HBM; the step moves the inputs once for the walk and "
+                "k, v of 7/8 of the tokens a second time for the segment-state pre-pass",
+    }
+
+    # ---- decode (config 5)
+    c5 = W.CONFIG5
+    state0, gamma5, steps_it = W.decode_stream(c5)
+    S = state0.to(dev)
+    gamma5 = gamma5.to(dev)
+    qkv = [tuple(t.to(dev) for t in next(steps_it)) for _ in range(4)]
+    o = torch.empty((c5.B, c5.H, c5.d), dtype=torch.float32, device=dev)
+    b5 = c5.B * c5.H * (2 * c5.d * c5.d * 4 + 3 * c5.d * 2 + c5.d * 4)
+    turn = [0]
+
+    def decode_step(states, store):
+        def fn():
+            i = turn[0]
+            turn[0] += 1
+            binding.leet_attn_decode_step_rd(*qkv[i % 4], gamma5, states[i % len(states)], o, store=store)
+        return fn
+
+    def decode_entry(us):
+        return {"us_per_step": us, "achieved_GBps": b5 / (us * 1e-6) / 1e9, "hbm_frac": b5 / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+
+    policies = (("auto", binding.DECODE_STORE_AUTO), ("cached", binding.DECODE_STORE_CACHED), ("streamed", binding.DECODE_STORE_STREAM))
+    resident = {name: timed(decode_step([S], code), 100, c5.steps) * 1e3 for name, code in policies}
+    us5 = resident["auto"]
+    extra["decode"] = {
+        "workload": c5.name, "steps": c5.steps, "warmup": 100, "us_per_step": us5, "tokens_per_s": c5.B / (us5 * 1e-6),
+        "store_policy": "auto (the library default: streamed for a state of 64 MiB or more)",
+        "roofline": {"kernel": "decode_kernel<128,128,bf16>", "bound": "hbm",
+                     "achieved": b5 / (us5 * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": b5 / (us5 * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": load_traffic(binding, c5.name, "decode"),
+                     "algorithmic_bytes_per_launch": b5,
+                     "note": "256 back-to-back steps on one 128 MiB state"},
+        "by_store_policy": {name: decode_entry(us) for name, us in resident.items()},
+    }
+    # the same step over three distinct 128 MiB state buffers in turn (384 MiB > the 256 MB
+    # Infinity Cache), so that every step streams its state from and to HBM
+    cold = [S, S.clone(), S.clone()]
+    extra["decode_cold"] = {
+        "workload": c5.name + ", three state buffers in rotation (every step streams from and to HBM)",
+        "steps": c5.steps, "warmup": 99,
+        "by_store_policy": {name: decode_entry(timed(decode_step(cold, code), 99, c5.steps) * 1e3) for name, code in policies},
+    }
+    extra["decode_cold"]["default_store_policy"] = extra["decode_cold"]["by_store_policy"]["auto"]
+    del S, qkv, o, cold
+
+    # ---- the fp32 kernel: config 2, and the headline shape with fp32 inputs.  Roofline: fp32 MFMA,
+    # priced with the flops the method needs (4 d^2 + 2*64*d per token-head), not the issued ones.
+    extra["fp32"] = {}
+    for cfgf in (W.CONFIG2, W.ForwardConfig("cfg3_shape_f32", cfg3.B, cfg3.H, cfg3.N, cfg3.d, "f32", cfg3.seed, cfg3.gamma_kind)):
+        qf, kf, vf, gf = (t.to(dev) for t in W.make_forward_inputs(cfgf))
+        of = torch.empty((cfgf.B, cfgf.H, cfgf.N, cfgf.d), dtype=torch.float32, device=dev)
+        msf = timed(lambda: binding.leet_attn_forward_ex(qf, kf, vf, gf, out=of), 100, 200)
+        kmsf = kernel_times(binding, qf, kf, vf, gf, of, 10, 0)
+        ff, bf = alg_flops_forward(cfgf), alg_bytes_forward(cfgf, 4)
+        nsegf, _ = binding.query_plan(cfgf.B, cfgf.H, cfgf.N, cfgf.d, binding.LEET_F32)
+        extra["fp32"][cfgf.name] = {
+            "B": cfgf.B, "H": cfgf.H, "N": cfgf.N, "d": cfgf.d, "segments": nsegf, "steps": 200, "warmup": 100,
+            "ms_per_step": msf, "tokens_per_s": cfgf.B * cfgf.N / (msf * 1e-3),
+            "kernel_ms": {"segment_state_prepass": kmsf[0], "segment_scan": kmsf[1], "chunk_walk": kmsf[2]},
+            "hbm_frac_whole_step": bf / (msf * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "roofline": {"kernel": f"fwd_f32_kernel<{cfgf.d}> (pre-pass + scan + walk: the whole step)", "bound": "mfma",
+                         "achieved": ff / (msf * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": ff / (msf * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, "traffic": None,
+                         "algorithmic_flops_per_step": ff},
+        }
+        del qf, kf, vf, of
+
+    # ---- the two element-wise comparison kernels on the headline workload (vector ALUs only):
+    # 3 multiply-adds = 5 flops per (token, rank index, value column)
+    q3, k3, v3, g3 = (t.to(dev) for t in W.make_forward_inputs(cfg3))
+    o3 = torch.empty((cfg3.B, cfg3.H, cfg3.N, cfg3.d), dtype=torch.float32, device=dev)
+    alu_flops = 5.0 * cfg3.B * cfg3.H * cfg3.N * cfg3.d * cfg3.d
+    extra["elementwise_methods"] = {"workload": cfg3.name, "flops_per_call": alu_flops, "steps": 60, "warmup": 30}
+    for name, fn in (("row_based", binding.leet_attn_forward_recurrent), ("fleet_attention", binding.leet_attn_forward_fleet)):
+        ms_e = timed(lambda: fn(q3, k3, v3, g3, out=o3), 30, 60)
+        extra["elementwise_methods"][name] = {
+            "ms_per_call": ms_e, "tokens_per_s": tokens3 / (ms_e * 1e-3),
+            "roofline": {"kernel": "elementwise_kernel<128,128,bf16,16,%s>" % ("rank-major" if name == "fleet_attention" else "token-major"),
+                         "bound": "alu", "achieved": alu_flops / (ms_e * 1e-3) / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": alu_flops / (ms_e * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, "traffic": None},
+        }
+    del q3, k3, v3, o3
+    return extra
+
+
+def cpu_baseline(W, cfg, tokens):
+    """The fp64 oracle as it stands, timed on this host's cores: a reported baseline, not a target."""
+    import ctypes
+
+    import numpy as np
+
+    import oracle
+
+    threads = oracle.max_threads()
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")   # the OpenMP runtime the oracle is linked with
+    except OSError:
+        gomp = None
+
+    def with_threads(n, fn):
+        if gomp is not None:
+            gomp.omp_set_num_threads(int(n))
+        try:
+            t0 = time.perf_counter()
+            fn()
+            return time.perf_counter() - t0
+        finally:
+            if gomp is not None:
+                gomp.omp_set_num_threads(int(threads))
+
+    qc, kc, vc, gc = W.make_forward_inputs(cfg)
+    q64, k64, v64, g64 = (W.to_f64(t) for t in (qc, kc, vc, gc))
+    best = min(with_threads(threads, lambda: oracle.recurrent(q64, k64, v64, g64)) for _ in range(3))
+    base = {
+        "value": tokens / best, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"whole {cfg.name} workload, fp64 recurrent form (Alg. 1 with decay), all threads, best of 3, {best:.2f} s",
+    }
+    others = {}
+    if gomp is not None:
+        # one thread: the first batch element (16 of the 64 sequences), scaled to tokens of the whole job
+        t1 = with_threads(1, lambda: oracle.recurrent(q64[:1], k64[:1], v64[:1], g64))
+        others["recurrent_one_thread"] = {"value": cfg.N / t1, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                          "sample": f"batch element 0 of {cfg.name} (16 heads x {cfg.N} tokens), {t1:.2f} s"}
+    # the quadratic form (Eq. "BCMV" written out): configs 1 and 2 whole, config 3 on sampled rows
+    for c in (W.CONFIG1, W.CONFIG2):
+        a, b, c_, g = (W.to_f64(t) for t in W.make_forward_inputs(c))
+        tq = with_threads(threads, lambda: oracle.quadratic(a, b, c_, g))
+        tr = with_threads(threads, lambda: oracle.recurrent(a, b, c_, g))
+        others[f"{c.name}"] = {"quadratic": {"value": c.B * c.N / tq, "unit": "tokens/s", "cores": threads, "seconds": tq},
+                               "recurrent": {"value": c.B * c.N / tr, "unit": "tokens/s", "cores": threads, "seconds": tr},
+                               "kind": "oracle", "sample": f"whole {c.name} workload"}
+    rng = np.random.default_rng(0)
+    rows = np.stack([rng.integers(0, cfg.B * cfg.H, 512), rng.integers(0, cfg.N, 512)], axis=1)
+    tq = with_threads(threads, lambda: oracle.quadratic_rows(q64, k64, v64, g64, rows))
+    # a row i costs i+1 key steps; the whole workload has B*H*N*(N+1)/2 of them
+    steps_done = float((rows[:, 1] + 1).sum())
+    steps_all = cfg.B * cfg.H * cfg.N * (cfg.N + 1) / 2.0
+    others["quadratic_sampled_rows"] = {
+        "value": tokens / (tq * steps_all / steps_done), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"512 random output rows of {cfg.name} by the quadratic form, {tq:.2f} s, scaled by the share of key steps they cover",
+    }
+    # the decode oracle on a bounded sample of config 5: 8 of its 256 steps
+    c5 = W.CONFIG5
+    state0, g5, it5 = W.decode_stream(c5)
+    S64 = np.ascontiguousarray(W.to_f64(state0))
+    g5 = W.to_f64(g5)
+    sample = [tuple(W.to_f64(t) for t in next(it5)) for _ in range(8)]
+    t0 = time.perf_counter()
+    for q5, k5, v5 in sample:
+        oracle.decode_step(q5, k5, v5, g5, S64)
+    dt5 = time.perf_counter() - t0
+    base["decode"] = {
+        "value": c5.B * len(sample) / dt5, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"8 of the 256 steps of {c5.name}, fp64 decode step, {dt5:.2f} s",
+    }
+    base["other_forms"] = others
+    return base
 
 
 if __name__ == "__main__":

@@ -341,13 +341,21 @@ __global__ __launch_bounds__(DV * 2, DV > 128 ? 1 : 2) void fwd_16bit_kernel(Fwd
                         u32x2 val = {E::pack2(o[it][4 * qd], o[it][4 * qd + 1]), E::pack2(o[it][4 * qd + 2], o[it][4 * qd + 3])};
                         *reinterpret_cast<u32x2*>(scr + ln * 20 + 4 * qd + 2 * g) = val;
                     }
+                    // both reads before the first store; a full chunk stores without per-row conditions
+                    u32x4 val[2];
 #pragma unroll
-                    for (int m = 0; m < 2; ++m) {
-                        const int row = 16 * m + (l >> 2);
-                        const u32x4 val = *reinterpret_cast<const u32x4*>(scr + row * 20 + 4 * (l & 3));
-                        const int i = 32 * it + row;
-                        if (i >= shift)
-                            __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(ob16 + (size_t)(tok0 - shift + i) * DV + 32 * w + 8 * (l & 3)));
+                    for (int m = 0; m < 2; ++m) val[m] = *reinterpret_cast<const u32x4*>(scr + (16 * m + (l >> 2)) * 20 + 4 * (l & 3));
+                    uint16_t* orow = ob16 + (size_t)tok0 * DV + 32 * w + 8 * (l & 3);
+                    if (shift == 0) {
+#pragma unroll
+                        for (int m = 0; m < 2; ++m)
+                            __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(orow + (size_t)(32 * it + 16 * m + (l >> 2)) * DV));
+                    } else {
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) {
+                            const int i = 32 * it + 16 * m + (l >> 2);
+                            if (i >= shift) __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(orow + (size_t)(i - shift) * DV));
+                        }
                     }
                 }
             } else {
@@ -363,13 +371,23 @@ __global__ __launch_bounds__(DV * 2, DV > 128 ? 1 : 2) void fwd_16bit_kernel(Fwd
                         f32x4 val = {o[it][4 * qd], o[it][4 * qd + 1], o[it][4 * qd + 2], o[it][4 * qd + 3]};
                         *reinterpret_cast<f32x4*>(scr + ln * 36 + 8 * qd + 4 * g) = val;
                     }
+                    // All four reads before the first store (a read placed under its row's condition makes
+                    // every store wait for its own LDS round trip); a full chunk, the common case, stores
+                    // without per-row conditions.
+                    f32x4 val[4];
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        const int row = 8 * m + (l >> 3);
-                        const f32x4 val = *reinterpret_cast<const f32x4*>(scr + row * 36 + 4 * (l & 7));
-                        const int i = 32 * it + row;
-                        if (i >= shift)
-                            __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(ob + (size_t)(tok0 - shift + i) * DV + 32 * w + 4 * (l & 7)));
+                    for (int m = 0; m < 4; ++m) val[m] = *reinterpret_cast<const f32x4*>(scr + (8 * m + (l >> 3)) * 36 + 4 * (l & 7));
+                    float* orow = ob + (size_t)tok0 * DV + 32 * w + 4 * (l & 7);
+                    if (shift == 0) {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m)
+                            __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(orow + (size_t)(32 * it + 8 * m + (l >> 3)) * DV));
+                    } else {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const int i = 32 * it + 8 * m + (l >> 3);
+                            if (i >= shift) __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(orow + (size_t)(i - shift) * DV));
+                        }
                     }
                 }
             }

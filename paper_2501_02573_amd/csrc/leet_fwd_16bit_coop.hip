@@ -451,28 +451,50 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         const int cshift = (c == n - 1) ? last_shift : 0;
         // offset of the chunk's first token (tile row cshift); rows are counted from there
         const size_t tile_off = (size_t)(tok_begin + c * kChunk) * DV + c0;
+        // All LDS reads of the tile are issued before the first store (a read placed under its row's
+        // condition would make every store wait for its own read: eight LDS round trips in a row);
+        // a full chunk, the common case, stores without any per-row condition.
         if (!kOut16) {
             // 128-byte row pieces: lane -> (row l/8 of eight rows, 16 bytes l%8)
             float* oc = og + tile_off + 4 * (l & 7);
             const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
+            f32x4 val[8];
 #pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                const int row = 8 * m + (l >> 3);  // row of the 64-row chunk tile; row block m / 4
-                const f32x4 val = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(oc + (size_t)(row - cshift) * DV));
+            for (int m = 0; m < 8; ++m) val[m] = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
+            if (cshift == 0) {
+#pragma unroll
+                for (int m = 0; m < 8; ++m)   // row 8 m + l/8 of the 64-row chunk tile; row block m / 4
+                    __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(oc + (size_t)(8 * m + (l >> 3)) * DV));
+            } else {
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const int row = 8 * m + (l >> 3);
+                    if (row >= cshift) __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(oc + (size_t)(row - cshift) * DV));
+                }
             }
         } else {
             // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
             uint16_t* oc = og16 + tile_off + 8 * (l & 3);
             const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 2) * 36 + 8 * (l & 3)];
+            u32x4 val[4];
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const int row = 16 * m + (l >> 2);  // row block m / 2
                 const float* src = ot + (m >> 1) * (32 * 36) + (16 * (m & 1)) * 36;
                 const f32x4 a = *reinterpret_cast<const f32x4*>(src);
                 const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
-                const u32x4 val = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
-                if (row >= cshift) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(oc + (size_t)(row - cshift) * DV));
+                const u32x4 v8 = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
+                val[m] = v8;
+            }
+            if (cshift == 0) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m)   // row 16 m + l/4; row block m / 2
+                    __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(oc + (size_t)(16 * m + (l >> 2)) * DV));
+            } else {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int row = 16 * m + (l >> 2);
+                    if (row >= cshift) __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(oc + (size_t)(row - cshift) * DV));
+                }
             }
         }
     };

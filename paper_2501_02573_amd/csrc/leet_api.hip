@@ -72,6 +72,25 @@ int wide_pre_split(long BH, int nseg, int seg_chunks) {
     return (nseg > 1 && seg_chunks >= 16 && seg_chunks % 2 == 0 && BH * (nseg - 1) <= 256) ? 2 : 1;
 }
 
+// The fp32 pre-pass is bound by fp32 MFMA issue, so what counts is how evenly its workgroups fill
+// the 256 compute units: it runs on segments `split` times finer than the walk's, with the split
+// (1, 2, 4 or 8 parts of at least two chunks) that needs the fewest chunk-times -- rounds of 256
+// workgroups x chunks per workgroup, a tenth less once two workgroups share a compute unit and
+// overlap -- plus half a chunk-time per part for the longer scan (B4 H16 N4096 d128 in fp32: 192
+// workgroups of 16 chunks take 93 us, 384 of 8 chunks 85 us, 768 of 4 chunks 73 us).
+int f32_pre_split(long BH, int nseg, int seg_chunks) {
+    if (nseg <= 1) return 1;
+    const long units = BH * (nseg - 1);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int split = 1; split <= 8; split *= 2) {
+        if (seg_chunks % split != 0 || (split > 1 && seg_chunks / split < 2)) break;
+        const double cost = (double)((units * split + 255) / 256) * (seg_chunks / split) * (split > 1 ? 0.9 : 1.0) + 0.5 * split;
+        if (split == 1 || cost < best_cost) { best = split; best_cost = cost; }
+    }
+    return best;
+}
+
 // Cost model of the 16-bit shapes, in microseconds, for one (kernel, segment
 // count) pair.  Each kernel is priced as the smooth maximum (x^p + y^p)^(1/p) of its dependent
 // chain (rounds of resident workgroups x chunks per segment x the per-chunk time of a lone
@@ -154,7 +173,7 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, int choic
         plan->coop = coop;
         plan->nseg = nseg;
         plan->seg_chunks = seg_chunks;
-        plan->pre_split = (dtype != LEET_F32 && !coop) ? wide_pre_split(BH, nseg, seg_chunks) : 1;
+        plan->pre_split = coop ? 1 : dtype != LEET_F32 ? wide_pre_split(BH, nseg, seg_chunks) : f32_pre_split(BH, nseg, seg_chunks);
         // one state per boundary the pre-pass computes, and, with segments, one more per sequence:
         // the scan's copy of the entering state, which the walk reads instead of the caller's buffer
         const size_t slots = nseg > 1 ? (size_t)(nseg - 1) * plan->pre_split + 1 : 0;
@@ -380,7 +399,7 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     auto launch_states = [&]() {
         return coop   ? leet::launch_fwd_16bit_coop_states(p, (int)BH, d, dv, f16, s)
                : in16 ? leet::launch_fwd_16bit_states(pre, (int)BH, d, dv, f16, s)
-                      : leet::launch_fwd_f32_states(p, (int)BH, d, s);
+                      : leet::launch_fwd_f32_states(pre, (int)BH, d, s);
     };
     auto launch_scan = [&]() {
         return leet::launch_seg_scan(p.seg_state, state_in, state_copy, gamma, (int)BH, H, pre.nseg, pre.seg_chunks * kChunk,

@@ -34,13 +34,15 @@
 
 namespace leet {
 
-template <int D>
+// The pre-pass (kOut = false) reads no Q and forms no scores: without those two members its
+// workgroups are small enough for two to share a compute unit at d = 128.
+template <int D, bool kOut>
 struct F32Smem {
     static constexpr int RS = D + 4;  // padded row stride (floats)
-    float q[kChunk * RS];
+    float q[kOut ? kChunk * RS : 4];
     float k[kChunk * RS];
     float v[kChunk * RS];
-    f32x4 pfrag[10][64];              // masked P^T tiles: [tile][lane], registers 0..3
+    f32x4 pfrag[kOut ? 10 : 1][64];   // masked P^T tiles: [tile][lane], registers 0..3
     float pw[kChunk + 4];             // gamma^n, n = 0..64
 };
 
@@ -50,16 +52,16 @@ __device__ __forceinline__ constexpr int f32_tile_jt(int n) { return n - (f32_ti
 
 // kOut = true : full walk (outputs + state).   kOut = false : state only (segment pre-pass).
 template <int D, bool kOut>
-__global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
+__global__ __launch_bounds__(D * 4, (kOut || D < 128) ? 2 : 4) void fwd_f32_kernel(FwdParams p) {
     constexpr int NT = D * 4;                  // threads: one wave per 16 value columns
     constexpr int NW = D / 16;                 // waves
     constexpr int DT = D / 16;                 // 16-row tiles of the key dimension
-    constexpr int RS = F32Smem<D>::RS;
+    constexpr int RS = F32Smem<D, kOut>::RS;
     constexpr int PR = D / 4;                  // 16-byte pieces per row
     constexpr int NLOAD = kChunk * PR / NT;    // pieces per thread per tensor (= 4)
     constexpr int ROWS_PER_PASS = NT / PR;     // rows one pass of all threads covers (= 16)
     constexpr int NSLOT = (10 + NW - 1) / NW;  // score tiles per wave, at most
-    __shared__ __attribute__((aligned(16))) F32Smem<D> sm;
+    __shared__ __attribute__((aligned(16))) F32Smem<D, kOut> sm;
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, ln = l & 15, qd = l >> 4;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
         const float* src = nullptr;
         if (kOut) {
             if (seg == 0) src = p.state_in ? p.state_in + (size_t)bh * D * D : nullptr;
-            else src = p.seg_state + ((size_t)bh * (p.nseg - 1) + (seg - 1)) * D * D;
+            else src = p.seg_state + ((size_t)bh * p.state_slots + (seg * p.state_step - 1)) * D * D;
         }
 #pragma unroll
         for (int t = 0; t < DT; ++t)
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(D * 4) void fwd_f32_kernel(FwdParams p) {
     if (kOut) {
         if (seg == p.nseg - 1 && p.state_out) dst = p.state_out + (size_t)bh * D * D;
     } else {
-        dst = p.seg_state + ((size_t)bh * (p.nseg - 1) + seg) * D * D;
+        dst = p.seg_state + ((size_t)bh * p.state_slots + seg) * D * D;
     }
     if (dst) {
 #pragma unroll

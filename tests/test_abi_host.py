@@ -62,6 +62,8 @@ def test_workspace_bytes_plan(lib):
     # with segments: one state per boundary, plus one per sequence for the copy of the entering state
     assert b.workspace_bytes(1, 1, 256, 64, b.LEET_F32) == (3 + 1) * 64 * 64 * 4  # fp32, short sequence: four segments of one chunk
     assert b.workspace_bytes(1, 1, 8192, 64, b.LEET_F32) == (63 + 1) * 64 * 64 * 4  # fp32, long sequence: segments of two chunks
+    # fp32, long segments: the pre-pass computes its states on quarter-segments (3 boundaries x 4 + the copy)
+    assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_F32) == 4 * 16 * (12 + 1) * 128 * 128 * 4
     assert b.workspace_bytes(1, 1, 256, 64, b.LEET_BF16) == 0
     assert b.workspace_bytes(4, 16, 4096, 128, b.LEET_BF16, 1) == 0
     # s segments -> (s-1) boundary states of d*d floats per (b,h), and the entering-state copy
@@ -171,7 +173,7 @@ def test_planner_against_measured_sweep(lib):
 def test_planner_invariants_on_random_shapes(lib):
     """Whatever the cost model prefers, a plan is well-formed: between 1 and ceil(N/64) segments,
     a caller's segment count honoured up to rounding, and a workspace of one state per segment
-    boundary (two on the wide 16-bit path when it computes them on half-segments)."""
+    boundary (two on the wide 16-bit and fp32 paths when they compute them on half-segments)."""
     import random
     from paper_2501_02573_amd import binding as b
     rng = random.Random(7)
@@ -195,8 +197,10 @@ def test_planner_invariants_on_random_shapes(lib):
         assert ws % state == 0
         slots = ws // state
         extra = 1 if nseg > 1 else 0    # the copy of the entering state
-        if kern == b.KERNEL_COLUMN_SPLIT or dtype == b.LEET_F32:
+        if kern == b.KERNEL_COLUMN_SPLIT:
             assert slots == nseg - 1 + extra
+        elif dtype == b.LEET_F32:      # the fp32 pre-pass runs on segments 1, 2, 4 or 8 times finer than the walk's
+            assert slots in [m * (nseg - 1) + extra for m in (1, 2, 4, 8)]
         else:
             assert slots in (nseg - 1 + extra, 2 * (nseg - 1) + extra)
 

@@ -409,7 +409,7 @@ def extra_legs(torch, binding, W, dev, cfg3, tokens3, use_graph):
     us5 = resident["auto"]
     extra["decode"] = {
         "workload": c5.name, "steps": c5.steps, "warmup": 100, "us_per_step": us5, "tokens_per_s": c5.B / (us5 * 1e-6),
-        "store_policy": "auto (the library default: streamed for a state of 64 MiB or more)",
+        "store_policy": "auto (the library default: a state of 64 MiB or more is cached when the previous decode call stepped the same buffer, streamed otherwise)",
         "roofline": {"kernel": "decode_kernel<128,128,bf16>", "bound": "hbm",
                      "achieved": b5 / (us5 * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": b5 / (us5 * 1e-6) / 1e9 / HBM_PEAK_GBS,

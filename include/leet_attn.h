@@ -270,11 +270,13 @@ int leet_attn_get_bf16_kernel(void);
 
 /*
  * Tuning knob: how a decode step stores the updated state.
- *   LEET_DECODE_STORE_AUTO    (default) streamed when this call's state is a quarter of the 256 MB
- *                             last-level cache or more, cached otherwise.  The library cannot see
- *                             whether other states are stepped in between; streaming a state that
- *                             would have stayed cached costs about 5 %, caching one that is
- *                             displaced before its next step about 20 %
+ *   LEET_DECODE_STORE_AUTO    (default) a state under a quarter of the 256 MB last-level cache is
+ *                             cached.  A larger one is cached only when it is being stepped alone --
+ *                             the previous decode call on this device updated this very buffer, and
+ *                             it fits half of the cache -- and streamed otherwise (another state came
+ *                             in between, or this is its first step).  Streaming a state that would
+ *                             have stayed cached costs about 5 %, caching one that is displaced
+ *                             before its next step about 20 %
  *   LEET_DECODE_STORE_CACHED  ordinary stores: best when the next step on the same state finds it
  *                             in the cache (one small model stepping alone)
  *   LEET_DECODE_STORE_STREAM  nontemporal stores: best when other states are touched before this one

@@ -53,6 +53,9 @@ std::atomic<int> g_bf16_kernel{LEET_KERNEL_AUTO};
 // Decode-state store policy: a leet_decode_store value.
 std::atomic<int> g_decode_store{LEET_DECODE_STORE_AUTO};
 
+// The state buffer of the previous decode call on each device (what AUTO's store policy looks at).
+std::atomic<const void*> g_last_decode_state[kMaxDevices];
+
 bool kernel_choice_ok(int c) { return c == LEET_KERNEL_WIDE || c == LEET_KERNEL_COLUMN_SPLIT || c == LEET_KERNEL_AUTO; }
 bool decode_store_ok(int m) { return m == LEET_DECODE_STORE_AUTO || m == LEET_DECODE_STORE_CACHED || m == LEET_DECODE_STORE_STREAM; }
 
@@ -617,16 +620,20 @@ int leet_attn_decode_step_v3(const void* q, const void* k, const void* v, const 
     status = current_device(&dev);
     if (status != LEET_OK) return status;
     const int elem = dtype == LEET_F32 ? 0 : dtype == LEET_BF16 ? 1 : 2;
-    // AUTO cannot see whether other states (other layers of a model) are touched before this one is
-    // stepped again, so it weighs the two mistakes: streaming a state that would have stayed in the
-    // last-level cache costs 5 % (128 MiB stepped alone: 41.8 against 39.9 us), caching one that is
-    // displaced before its next step costs 20 % (three 128 MiB states in turn: 53 against 44 us;
-    // 512 MiB: 6.4 against 5.1 TB/s).  A state of a quarter of that cache or more is therefore
-    // streamed; smaller ones, which also survive next to a few neighbours, are stored normally.
+    // AUTO.  A small state (under a quarter of the last-level cache) is stored normally: it survives
+    // there next to a few neighbours.  A larger one is worth caching only if nothing displaces it
+    // before its next step -- 5 % gained (128 MiB stepped alone: 39.9 against 41.8 us), against 20 %
+    // lost when it is displaced (three 128 MiB states in turn: 53 against 44 us; 512 MiB: 5.1 against
+    // 6.4 TB/s).  The library cannot see the caller's other work, but it can see its own: if the
+    // previous decode call on this device stepped this very buffer, and the state fits half of the
+    // cache, it is being stepped alone and is cached; in every other case (another layer's state
+    // came in between, or this is the first step) it is streamed.
+    const size_t state_bytes = (size_t)BH * d * dv * sizeof(float);
+    const void* prev_state = g_last_decode_state[dev].exchange(state_inout, std::memory_order_relaxed);
     const int store_mode = store == LEET_CHOICE_DEFAULT ? g_decode_store.load(std::memory_order_relaxed) : store;
-    const bool stream_store = store_mode == LEET_DECODE_STORE_STREAM ||
-                              (store_mode == LEET_DECODE_STORE_AUTO &&
-                               (size_t)BH * d * dv * sizeof(float) >= kLastLevelCacheBytes / 4);
+    bool stream_store = store_mode == LEET_DECODE_STORE_STREAM;
+    if (store_mode == LEET_DECODE_STORE_AUTO && state_bytes >= kLastLevelCacheBytes / 4)
+        stream_store = !(prev_state == state_inout && state_bytes <= kLastLevelCacheBytes / 2);
     hipError_t e = leet::launch_decode(q, k, v, gamma, state_inout, out, (int)BH, H, d, dv, elem, stream_store,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;

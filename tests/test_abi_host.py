@@ -101,6 +101,18 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert ex(p, p, p, p, p, odd, None, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
 
 
+def test_profile_entry_rejects_state_handed_on_in_place(lib):
+    """The timing aid launches the walk several times; with state_out aliasing state_in the later
+    launches would start from the wrong state, so it refuses (on the host, before any device call)."""
+    from paper_2501_02573_amd import binding as b
+    p = ctypes.c_void_p(0x1000)
+    s = ctypes.c_void_p(0x2000)
+    ms = (ctypes.c_float * 3)()
+    prof = lib.leet_attn_forward_profile
+    assert prof(p, p, p, p, p, s, s, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None, ms) == b.LEET_ERR_INVALID_ARG
+    assert prof(p, p, p, p, p, s, s, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None, None) == b.LEET_ERR_INVALID_ARG
+
+
 def test_kernel_choice_setter_and_plan_query(lib):
     from paper_2501_02573_amd import binding as b
     assert b.get_bf16_kernel() == b.KERNEL_AUTO

@@ -29,8 +29,13 @@
  *     LEET_ERR_LAUNCH no buffer has been written.  LEET_ERR_LAUNCH means the HIP
  *     runtime failed part-way; the contents of the output buffers are then undefined.
  *   - d must be 64 or 128 (the _rd entry points also take rank 128 with value width
- *     256).  B, H, N >= 1.  N need not be a multiple of the chunk length (64
+ *     256).  B, H >= 1.  N need not be a multiple of the chunk length (64
  *     tokens); the last chunk may be ragged.
+ *   - A prefill over no tokens is legal (N = 0; N < 0 is LEET_ERR_INVALID_ARG): the loop over
+ *     chunks (Alg. 2) does not run, so nothing is written to `out`, and `state_out`, when
+ *     given, receives the entering state unchanged (zero if `state_in` is NULL).  q, k, v and
+ *     out are then empty and may be NULL.  It needs no workspace; the plan query reports zero
+ *     segments.  The decode step has no length and always processes one token.
  *   - Outputs that the library will not read again (prefill `out`) are written
  *     with nontemporal stores, so that they do not displace the inputs from the
  *     caches; this changes no value.

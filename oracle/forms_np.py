@@ -70,7 +70,7 @@ def chunked(q, k, v, gamma, chunk: int, state_in: Optional[np.ndarray] = None
 def _lambda_cumsum(x: np.ndarray, lam: float) -> np.ndarray:
     """y_i = x_i + lam * y_{i-1} along axis 0 (Appendix C.1)."""
     y = np.empty_like(x)
-    acc = np.zeros_like(x[0])
+    acc = np.zeros(x.shape[1:], dtype=x.dtype)
     for i in range(x.shape[0]):
         acc = x[i] + lam * acc
         y[i] = acc

@@ -61,7 +61,9 @@ int leet_oracle_quadratic_rd(const double *q, const double *k, const double *v,
                              const double *gamma, double *out,
                              int B, int H, long N, int r, int dv)
 {
-    if (!q || !k || !v || !gamma || !out || B <= 0 || H <= 0 || N <= 0 || r <= 0 || dv <= 0) return 1;
+    if (!gamma || B <= 0 || H <= 0 || N < 0 || r <= 0 || dv <= 0) return 1;
+    if (N == 0) return 0; /* no rows */
+    if (!q || !k || !v || !out) return 1;
     long BH = (long)B * H;
 #pragma omp parallel for schedule(dynamic, 1) collapse(2)
     for (long bh = 0; bh < BH; ++bh) {
@@ -123,7 +125,9 @@ int leet_oracle_recurrent_rd(const double *q, const double *k, const double *v,
                              double *out, double *state_out,
                              int B, int H, long N, int r, int dv)
 {
-    if (!q || !k || !v || !gamma || !out || B <= 0 || H <= 0 || N <= 0 || r <= 0 || dv <= 0) return 1;
+    /* N = 0: the loop over tokens does not run and the state leaves as it entered */
+    if (!gamma || B <= 0 || H <= 0 || N < 0 || r <= 0 || dv <= 0) return 1;
+    if (N > 0 && (!q || !k || !v || !out)) return 1;
     long BH = (long)B * H;
     size_t ssz = (size_t)r * dv;
     int failed = 0;

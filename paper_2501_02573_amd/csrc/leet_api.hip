@@ -14,6 +14,7 @@
 namespace leet {
 hipError_t launch_fwd_16bit_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
 hipError_t launch_fwd_16bit_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
+hipError_t launch_state_pass(const float* state_in, float* state_out, int BH, int D, int DV, hipStream_t stream);
 hipError_t launch_fwd_16bit_coop_states(const FwdParams& p, int BH, int D, int DV, bool f16, hipStream_t stream);
 hipError_t launch_fwd_16bit_coop_walk(const FwdParams& p, int BH, int D, int DV, bool f16, bool out16, hipStream_t stream);
 hipError_t launch_fwd_f32_states(const FwdParams& p, int BH, int D, hipStream_t stream);
@@ -324,6 +325,18 @@ int own_workspace(int dev, size_t bytes, hipStream_t stream, void** out) {
 
 enum WorkspaceKind { kWsCallerOrOwned = 0, kWsStatic = 1 };
 
+// A prefill over no tokens (N = 0): nothing to compute and no output rows; the state leaves as it
+// entered, zero when none was given.  Touches the device only when a state has to be written.
+int empty_forward(const float* state_in, float* state_out, long BH, int d, int dv, void* stream, float* kernel_ms) {
+    if (kernel_ms) kernel_ms[0] = kernel_ms[1] = kernel_ms[2] = 0.0f;
+    if (!state_out || state_out == state_in) return LEET_OK;
+    int dev = 0;
+    const int status = current_device(&dev);
+    if (status != LEET_OK) return status;
+    const hipError_t e = leet::launch_state_pass(state_in, state_out, (int)BH, d, dv, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LEET_OK : LEET_ERR_LAUNCH;
+}
+
 int forward_impl(const void* q, const void* k, const void* v, const float* gamma, void* out,
                  const float* state_in, float* state_out, void* workspace, size_t workspace_bytes,
                  int segments, int B, int H, int N, int d, int dv, int dtype, int out_dtype, int mask,
@@ -332,8 +345,9 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     if (kernel_choice != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel_choice)) return LEET_ERR_INVALID_ARG;
     const bool no_decay = mask == LEET_MASK_CAUSAL;
-    if (!q || !k || !v || !out || (!gamma && !no_decay)) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N < 0 || d <= 0 || dv <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    // no tokens: q, k, v, out are empty and may be null
+    if ((N > 0 && (!q || !k || !v || !out)) || (!gamma && !no_decay)) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
     if (!shape_ok(d, dv, dtype, &status)) return status;
     // the output is fp32, or, for 16-bit inputs, the input type
@@ -345,13 +359,14 @@ int forward_impl(const void* q, const void* k, const void* v, const float* gamma
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return LEET_ERR_INVALID_ARG;
     const long BH = (long)B * H;
     if (BH >= (1L << 31) || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
+    // the timing aid relaunches the walk: with the state handed on in place, later launches would
+    // start from the state the first one left
+    if (kernel_ms && state_in && state_in == state_out) return LEET_ERR_INVALID_ARG;
+    if (N == 0) return empty_forward(state_in, state_out, BH, d, dv, stream, kernel_ms);
 
     Plan plan;
     if (!make_plan(BH, N, d, dv, dtype, segments, kernel_choice, &plan)) return LEET_ERR_TOO_LARGE;
     if (ws_kind == kWsStatic && plan.ws_bytes > kStaticScratchBytes) return LEET_ERR_SCRATCH_LIMIT;
-    // the timing aid relaunches the walk: with the state handed on in place, later launches would
-    // start from the state the first one left
-    if (kernel_ms && state_in && state_in == state_out) return LEET_ERR_INVALID_ARG;
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -461,8 +476,8 @@ int forward_elementwise(bool fleet, const void* q, const void* k, const void* v,
                         int dtype, int mask, void* stream) {
     if (mask != LEET_MASK_DECAY && mask != LEET_MASK_CAUSAL) return LEET_ERR_INVALID_ARG;
     if (mask == LEET_MASK_CAUSAL) gamma = nullptr;
-    if (!q || !k || !v || !out || (!gamma && mask == LEET_MASK_DECAY)) return LEET_ERR_INVALID_ARG;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N < 0 || d <= 0 || dv <= 0) return LEET_ERR_INVALID_ARG;
+    if ((N > 0 && (!q || !k || !v || !out)) || (!gamma && mask == LEET_MASK_DECAY)) return LEET_ERR_INVALID_ARG;
     int status = LEET_OK;
     if (!shape_ok(d, dv, dtype, &status)) return status;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(state_in) ||
@@ -470,6 +485,7 @@ int forward_elementwise(bool fleet, const void* q, const void* k, const void* v,
         return LEET_ERR_INVALID_ARG;
     const long BH = (long)B * H;
     if (BH >= (1L << 31) / 8 || (long)N > (1L << 30)) return LEET_ERR_TOO_LARGE;
+    if (N == 0) return empty_forward(state_in, state_out, BH, d, dv, stream, nullptr);
     int dev = 0;
     status = current_device(&dev);
     if (status != LEET_OK) return status;
@@ -545,7 +561,7 @@ size_t leet_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 size_t leet_attn_workspace_bytes_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel) {
     int status = LEET_OK;
-    if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;
+    if (B <= 0 || H <= 0 || N <= 0 || segments < 0 || !shape_ok(r, dv, dtype, &status)) return 0;  // N = 0 needs none
     if (kernel != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel)) return 0;
     Plan plan;
     if (!make_plan((long)B * H, N, r, dv, dtype, segments, kernel, &plan)) return 0;
@@ -582,9 +598,14 @@ int leet_attn_forward_recurrent(const void* q, const void* k, const void* v, con
 int leet_attn_query_plan_v3(int B, int H, int N, int r, int dv, int dtype, int segments, int kernel_choice,
                             int* nseg, int* kernel) {
     int status = LEET_OK;
-    if (B <= 0 || H <= 0 || N <= 0 || segments < 0) return LEET_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || N < 0 || segments < 0) return LEET_ERR_INVALID_ARG;
     if (kernel_choice != LEET_CHOICE_DEFAULT && !kernel_choice_ok(kernel_choice)) return LEET_ERR_INVALID_ARG;
     if (!shape_ok(r, dv, dtype, &status)) return status;
+    if (N == 0) {  // no tokens: no segment, no chunk kernel
+        if (nseg) *nseg = 0;
+        if (kernel) *kernel = LEET_KERNEL_WIDE;
+        return LEET_OK;
+    }
     Plan plan;
     if (!make_plan((long)B * H, N, r, dv, dtype, segments, kernel_choice, &plan)) return LEET_ERR_TOO_LARGE;
     if (nseg) *nseg = plan.nseg;

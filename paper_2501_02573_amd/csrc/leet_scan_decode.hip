@@ -61,6 +61,26 @@ hipError_t launch_seg_scan(float* seg_state, const float* state_in, float* state
 }
 
 // ---------------------------------------------------------------------------------
+// A prefill over no tokens: the loop of Alg. 1 / Alg. 2 does not run, so the state leaves as it
+// entered (zero when none is given).  One thread per four state elements.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void state_pass_kernel(const float* state_in, float* state_out, size_t total4) {
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total4) return;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (state_in) s = reinterpret_cast<const f32x4*>(state_in)[idx];
+    reinterpret_cast<f32x4*>(state_out)[idx] = s;
+}
+
+hipError_t launch_state_pass(const float* state_in, float* state_out, int BH, int D, int DV, hipStream_t stream) {
+    if (!state_out || state_out == state_in) return hipSuccess;
+    size_t total4 = (size_t)BH * D * DV / 4;
+    unsigned blocks = (unsigned)((total4 + 255) / 256);
+    hipLaunchKernelGGL(state_pass_kernel, dim3(blocks), dim3(256), 0, stream, state_in, state_out, total4);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
 // Decode step (Alg. 1, Appendix B.1, with the discounted update of Appendix C.1):
 //     S <- gamma S + k^T v ;  o = q S        per (batch, head), S is D x DV fp32
 // (D = width of q and k, DV = width of v and o; D = DV except for rank 128 / width 256).

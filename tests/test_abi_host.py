@@ -96,7 +96,14 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert dec(p, p, p, p, p, p, 1, 0, 64, None) == b.LEET_ERR_INVALID_ARG
     assert dec(p, p, p, p, p, p, 1, 1, 32, None) == b.LEET_ERR_UNSUPPORTED
     assert lib.leet_attn_decode_step_ex(p, p, p, p, p, p, 1, 1, 64, 5, None) == b.LEET_ERR_UNSUPPORTED
+    # no tokens: legal, q, k, v, out may be null, and with no state to write nothing touches a device
+    assert fwd(None, None, None, p, None, 1, 1, 0, 64, b.LEET_F32, None) == b.LEET_OK
+    assert fwd(None, None, None, None, None, 1, 1, 0, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG   # gamma still required
+    assert fwd(None, None, None, p, None, 1, 1, 0, 96, b.LEET_F32, None) == b.LEET_ERR_UNSUPPORTED
+    assert lib.leet_attn_workspace_bytes(1, 1, 0, 64, b.LEET_F32, 0) == 0
+    assert b.query_plan(4, 2, 0, 128, b.LEET_BF16) == (0, b.KERNEL_WIDE)
     ex = lib.leet_attn_forward_ex
+    assert ex(None, None, None, p, None, p, p, None, 0, 0, 1, 1, 0, 64, b.LEET_F32, None) == b.LEET_OK   # state handed on in place
     assert ex(p, p, p, p, p, None, None, None, 0, -1, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
     assert ex(p, p, p, p, p, odd, None, None, 0, 0, 1, 1, 64, 64, b.LEET_F32, None) == b.LEET_ERR_INVALID_ARG
 

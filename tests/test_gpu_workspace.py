@@ -197,3 +197,53 @@ def test_decode_store_policy_per_call(B):
     assert max_rel_err(results[0][1].cpu().numpy(), S_ref) < 1e-5
     with pytest.raises(B.LeetAttnError):
         B.leet_attn_decode_step_rd(*dev(q, k, v), dg, S, store=9)
+
+
+# ---------------------------------------------------------------- no tokens
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_empty_sequence_hands_the_state_on(B, dtype, d):
+    """N = 0 through every prefill entry point: no output rows, state_out = state_in bit for bit
+    (zero without one), and a prompt fed as [] + [all] equals one call; the oracle does the same."""
+    Bn, H, N = 2, 3, 150
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, dtype, seed=77)
+    s_in = (torch.randn(Bn, H, d, d, dtype=torch.float32) * 0.05)
+    dq, dk, dv, dg, ds_in = dev(q, k, v, gamma, s_in)
+    e = dq[:, :, :0].contiguous()
+    assert e.shape == (Bn, H, 0, d)
+    ref, s_ref = oracle.recurrent(*(W.to_f64(t) for t in (q, k, v, gamma)), state_in=W.to_f64(s_in))
+    e64 = np.zeros((Bn, H, 0, d))
+    _, s_or = oracle.recurrent(e64, e64, e64, W.to_f64(gamma), state_in=W.to_f64(s_in))
+    assert np.array_equal(s_or, W.to_f64(s_in))
+
+    calls = {
+        "forward_ex": lambda so, si: B.leet_attn_forward_ex(e, e, e, dg, state_in=si, state_out=so),
+        "forward_v2": lambda so, si: B.leet_attn_forward_v2(e, e, e, dg, state_in=si, state_out=so),
+        "forward_recurrent": lambda so, si: B.leet_attn_forward_recurrent(e, e, e, dg, state_in=si, state_out=so),
+        "forward_static": lambda so, si: B.leet_attn_forward_static(e, e, e, dg, torch.empty_like(e, dtype=torch.float32),
+                                                                   state_in=si, state_out=so),
+    }
+    for name, call in calls.items():
+        say(f"  {name}, N = 0")
+        s_out = torch.full_like(ds_in, 7.0)
+        out = call(s_out, ds_in)
+        torch.cuda.synchronize()
+        assert out is None or tuple(out.shape) == (Bn, H, 0, d)
+        assert torch.equal(s_out, ds_in), f"{name}: state not handed on unchanged"
+        s_out.fill_(7.0)
+        call(s_out, None)
+        torch.cuda.synchronize()
+        assert torch.count_nonzero(s_out).item() == 0, f"{name}: no entering state must give a zero state"
+        s_alias = ds_in.clone()
+        call(s_alias, s_alias)
+        torch.cuda.synchronize()
+        assert torch.equal(s_alias, ds_in), f"{name}: in-place hand-off changed the state"
+    assert B.leet_attn_forward(e, e, e, dg).shape == (Bn, H, 0, d)
+
+    # [] + [all] = [all]
+    s_mid = torch.empty_like(ds_in)
+    B.leet_attn_forward_ex(e, e, e, dg, state_in=ds_in, state_out=s_mid)
+    s_end = torch.empty_like(ds_in)
+    out = B.leet_attn_forward_ex(dq, dk, dv, dg, state_in=s_mid, state_out=s_end)
+    torch.cuda.synchronize()
+    check(out.cpu().numpy(), ref, dtype, "prompt after an empty piece vs oracle")
+    check(s_end.cpu().numpy(), s_ref, dtype, "state after [] + [all] vs oracle")

@@ -282,6 +282,33 @@ def test_state_carry_prefill_then_decode():
     assert np.allclose(sc, s_full, rtol=1e-12, atol=1e-13)
 
 
+def test_empty_sequence_leaves_the_state_as_it_entered():
+    """N = 0: the loops of Alg. 1 and Alg. 2 do not run.  No output rows; the state is handed on
+    unchanged (zero without an entering state); and a sequence split as [] + [all] or [all] + []
+    gives what one pass gives."""
+    B, H, N, d = 2, 3, 11, 8
+    q, k, v = rand_qkv(B, H, N, d)
+    gamma = np.array([0.9, 0.5, 1.0])
+    s_in = np.random.default_rng(5).standard_normal((B, H, d, d))
+    e = np.zeros((B, H, 0, d))
+    o, s = oracle.recurrent(e, e, e, gamma, state_in=s_in)
+    assert o.shape == (B, H, 0, d) and np.array_equal(s, s_in)
+    o, s = oracle.recurrent(e, e, e, gamma)
+    assert o.shape == (B, H, 0, d) and np.array_equal(s, np.zeros((B, H, d, d)))
+    assert oracle.quadratic(e, e, e, gamma).shape == (B, H, 0, d)
+    assert oracle.fleet(e, e, e, gamma).shape == (B, H, 0, d)
+    oc, sc = oracle.chunked(e, e, e, gamma, 4, state_in=s_in)
+    assert oc.shape == (B, H, 0, d) and np.array_equal(sc, s_in)
+    full, s_full = oracle.recurrent(q, k, v, gamma, state_in=s_in)
+    _, s0 = oracle.recurrent(e, e, e, gamma, state_in=s_in)
+    o1, s1 = oracle.recurrent(q, k, v, gamma, state_in=s0)
+    assert np.array_equal(o1, full) and np.array_equal(s1, s_full)
+    _, s2 = oracle.recurrent(e, e, e, gamma, state_in=s_full)
+    assert np.array_equal(s2, s_full)
+    with pytest.raises(Exception):
+        oracle.recurrent(np.zeros((B, H, 3, d)), np.zeros((B, H, 3, d)), np.zeros((B, H, 2, d)), gamma)
+
+
 # ---------------------------------------------------------------- planted mistakes are caught
 def _mutants():
     """Plausible wrong versions of form 2, written here (numpy), to show the pins above would fail on them."""

@@ -13,36 +13,38 @@
 // all of Q and K (the copies of one sequence are placed on one XCD so that all but one of
 // the reads hit its L2) and its own 32 columns of V, and writes its 32 columns of O.
 //
-// Inside a workgroup the waves are specialised, one 32x32 output tile per task, and hand
-// their products to one another through LDS in operand-register order:
+// Inside a workgroup the waves are specialised and hand their products to one another through
+// LDS in operand-register order.  What bounds an iteration is the LDS: every MFMA of a 32x32
+// tile takes 2 KB of operands from it, so the roles are cut such that operands shared by two
+// products are read once and stay in registers:
 //
-//   waves 0..2   G1  score tile n: P^T = K rows x Q rows, decay mask, pack -> pfrag[n]
-//                    (tiles (jt,it) = (0,0), (1,1), (0,1)); after that G4 for state tile n
-//   waves 3, 4   G3  O^T[c][i] = S^T Q^T for row block it = w-3 (S^T from LDS st[c][dk]),
-//                    rows scaled by gamma^(i+1); one iteration later G2: O^T += V^T P^T
-//                    (V through transposing LDS reads, P from pfrag), then the tile goes to
-//                    LDS for the store wave.  Wave 3, whose row block has one score tile to
-//                    fold in against wave 4's two, also owns state tile 3 (d = 128 only)
-//   wave  5      stores the finished O tiles in whole row pieces (and nothing else: its stores
-//                    queue behind the loaders' loads in the compute unit's one vector-memory
-//                    pipeline, which with 36 KB loaded and 8 KB stored per chunk is what the
-//                    iteration time comes down to)
+//   waves 0, 1   row block it = w of the chunk (32 tokens):
+//                G1  the masked score tiles of the row block, P^T = K rows x Q rows: the diagonal
+//                    tile (it, it) and, for it = 1, the tile (0, 1) below the diagonal
+//                G3  O^T[c][i] = S^T Q^T (S^T from LDS st[c][dk]), rows scaled by gamma^(i+1)
+//                G2  O^T += V^T P^T (V through transposing LDS reads, P^T straight from the G1
+//                    accumulators: a P^T accumulator, lane = query, registers = keys, is a B operand
+//                    as it is); the finished tile goes to LDS for the store wave.
+//                The Q rows are read once for all three products.
+//   waves 2, 3   G4  S[dk tile][c] = gamma^L S + K^T (Gam V) for two of the four 32-row state tiles
+//                    each (one of two at d = 64), A = K through transposing reads, B = the Gam-scaled
+//                    V copy, read once for both tiles; the owner keeps its fp32 tiles in accumulators
+//                    for the whole walk and publishes them in the input type as S^T[c][dk] for the
+//                    row waves of the next chunk
+//   waves 4, 5   store the finished O tile of row block w - 4 in whole row pieces (and nothing else:
+//                    their stores queue behind the loaders' loads in the compute unit's one
+//                    vector-memory pipeline)
 //   waves 6, 7   loaders: all global loads of the workgroup and the LDS writes of the tiles
-//   G4  S[dk tile][c] = gamma^L S + K^T (Gam V), A = K through transposing reads, B = the
-//       Gam-scaled V copy; the owner keeps its 32x32 fp32 tile in accumulators for the whole
-//       walk and publishes it in the input type as S^T[c][dk] for the G3 waves of the next chunk.
 //
 // A compute unit accepts only so many outstanding vector-memory requests, and a wave that
 // issues one more stalls at that instruction until there is room; a wave that both loads and
 // computes therefore spends the delivery time of its loads unable to compute.  Hence the
 // loader waves: they sit in that stall (and in the wait for the oldest register stage) while
-// the six compute waves run, and the only thing that ties the two together is one workgroup
-// barrier per chunk.  To get down to one barrier the chunk is software-pipelined: in
-// iteration t the score waves produce P(t) and S(t+1), the output waves finish chunk t-1
-// (G2 with P(t-1)) and then start chunk t (G3 with S(t)), wave 5 stores chunk t-2, and the
-// loaders write chunk t+1 to LDS and issue the loads of chunk t+3.  Q and K tiles, P fragments and S^T are
-// double-buffered in LDS, the V slice and its scaled copy triple-buffered (chunk t-1 is still
-// read in iteration t).
+// the compute waves run, and the only thing that ties the two together is one workgroup
+// barrier per chunk.  The chunk is software-pipelined over that barrier: in iteration t the row
+// waves produce O(t), the state waves S(t+1), the store waves write chunk t-1 to memory, and
+// the loaders write chunk t+1 to LDS and issue the loads of chunk t+3.  Q and K tiles, S^T and the
+// output tiles are double-buffered in LDS, the V slice and its scaled copy triple-buffered.
 //
 // MFMA conventions (32x32x16): an A (B) operand holds, in lane l, row (column) l%32 and the
 // eight contraction slots of group g = l/32; an accumulator holds, in lane l, column l%32
@@ -75,7 +77,6 @@ struct CoopSmem {
     uint16_t k[2][kChunk * RSQ];
     uint16_t v[3][kChunk * RSV];
     uint16_t vs[3][kChunk * RSVS];      // Gam V: row j scaled by gamma^(63-j)
-    u32x4 pfrag[2][3][2][64];           // masked P^T tiles as B operands: [buffer][tile][register half][lane]
     uint16_t st[2][32 * RST];
     float obuf[2][2][32 * 36];          // finished O tiles on their way out: [buffer][row block][row][column], padded rows
     float pw[kChunk + 4];               // gamma^n, n = 0..64
@@ -137,7 +138,7 @@ template <int D, int DV, bool kOut, typename E, bool kOut16>
 __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams p, int ngroups) {
     using namespace coop;
     auto mfma32 = [](u32x4 a, u32x4 b, f32x16 c) { return E::mfma32(a, b, c); };
-    constexpr int NT = kCoopThreads;            // six compute waves and the loader waves
+    constexpr int NT = kCoopThreads;            // two row waves, two state waves, two store waves and the loader waves
     constexpr int NL = 64 * kCoopLoaderWaves;   // loader threads (waves 6 and up)
     constexpr int NS = kCoopStages;             // register stages of the loaders
     constexpr int VPL = kChunk * 4 / NL;        // V pieces per loader thread per chunk
@@ -168,13 +169,14 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     const int c0 = 32 * slice;
 
     // ---- roles
-    const bool score_wave = kOut && w < 3;                       // G1 tile n = w
-    const bool out_wave = kOut && (w == 3 || w == 4);            // output row block it = w - 3
-    const int st_tile = (w < 4) ? w : -1;                        // state tile owned (G4), if it exists: waves 0..2 and output wave 3
-    const bool state_wave = st_tile >= 0 && st_tile < DT;
-    const bool store_wave = kOut && w == 5;                      // writes the finished O tiles to global memory, nothing else
+    constexpr int TPW = (DT >= 2) ? DT / 2 : 1;                  // state tiles per state wave
+    const bool row_wave = kOut && w < 2;                         // scores, G3 and G2 of row block it_own = w
+    const int it_own = w & 1;
+    const int tw = w - 2;                                        // state wave number
+    const bool state_wave = (w == 2 || w == 3) && tw * TPW < DT; // G4 for state tiles tw TPW .. tw TPW + TPW - 1
+    const int tile0 = max(tw, 0) * TPW;
+    const bool store_wave = kOut && (w == 4 || w == 5);          // writes the finished O tile of row block w - 4 to global memory
     const bool loader = w >= 6;
-    const int it_own = w - 3;
     const int lt = tid - (NT - NL);                              // loader thread index
 
     const int tok_begin = seg * p.seg_chunks * kChunk;
@@ -194,12 +196,14 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);
     }
 
-    // ---- state tile of this wave: S[r] = S[dk = 32 t + pi(m(r, g))][c = c0 + ln]
-    auto dk_of = [&](int r) {
+    // ---- state tiles of this wave: S[u][r] = S[dk = 32 (tile0 + u) + pi(m(r, g))][c = c0 + ln]
+    auto dk_of = [&](int u, int r) {
         // m = 8(r/4) + 4g + r%4 ; pi swaps the 4- and 8-bits: dk = 16(r/8) + 8g + 4((r/4)&1) + r%4
-        return 32 * st_tile + 16 * (r >> 3) + 8 * g + 4 * ((r >> 2) & 1) + (r & 3);
+        return 32 * (tile0 + u) + 16 * (r >> 3) + 8 * g + 4 * ((r >> 2) & 1) + (r & 3);
     };
-    f32x16 S = zero16();
+    f32x16 S[TPW];
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) S[u] = zero16();
     if (state_wave) {
         const float* src = nullptr;
         if (kOut) {
@@ -208,14 +212,19 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         }
         if (src) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] = src[dk_of(r) * DV + c0 + ln];
+            for (int u = 0; u < TPW; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[u][r] = src[dk_of(u, r) * DV + c0 + ln];
         }
     }
-    // S^T[c][dk] in LDS: registers 8h..8h+7 are dk = 32 t + 16 h + 8 g + (0..7)
-    const int st_wr_off = ln * RST + 32 * max(st_tile, 0) + 8 * g;  // + 16 h
+    // S^T[c][dk] in LDS: registers 8h..8h+7 of tile t are dk = 32 t + 16 h + 8 g + (0..7)
+    const int st_wr_off = ln * RST + 32 * tile0 + 8 * g;  // + 32 u + 16 h
     auto publish_state = [&](int buf) {
-        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off]) = pack_half<E>(S, 0);
-        *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 16]) = pack_half<E>(S, 1);
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+            *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 32 * u]) = pack_half<E>(S[u], 0);
+            *reinterpret_cast<u32x4*>(&sm.st[buf][st_wr_off + 32 * u + 16]) = pack_half<E>(S[u], 1);
+        }
     };
     if (kOut && state_wave) publish_state(0);
 
@@ -295,18 +304,19 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     };
 
     // ---- per-lane constants of the compute waves
-    // decay weights of the score tile this wave produces: i - j = 32 (it - jt) + ln - jr
-    f32x16 wgt = zero16();
-    if (score_wave) {
+    // decay weights of the two kinds of score tile, i - j = 32 (it - jt) + ln - jr: the diagonal
+    // tiles (jt = it) and the one below the diagonal (jt = 0, it = 1; row wave 1 only)
+    f32x16 wgt_d = zero16(), wgt_o = zero16();
+    if (row_wave) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int d = ln - (8 * (r >> 2) + 4 * g + (r & 3));
-            float diag = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
-            wgt[r] = (w == 2) ? sm.pw[32 + d] : diag;
+            wgt_d[r] = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
+            wgt_o[r] = sm.pw[32 + d];
         }
     }
-    const float lam_full = sm.pw[min(32 * max(it_own, 0) + ln + 1, kChunk)];  // gamma^(i+1) in a full chunk
-    const float gl_full = sm.pw[kChunk];                                       // gamma^64
+    const float lam_full = sm.pw[min(32 * it_own + ln + 1, kChunk)];  // gamma^(i+1) in a full chunk
+    const float gl_full = sm.pw[kChunk];                               // gamma^64
     const int row_off = ln * RSQ + 8 * g;  // 16-byte row fragments of Q, K: + 32 tile RSQ + 16 s
     // transposing reads: lane supplies row 4g + s16/4 (+ 16 f, + 8 for the second half) and four columns
     const int tr_off_v = (4 * g + (s16 >> 2)) * RSV + 16 * half + 4 * (s16 & 3);
@@ -314,172 +324,135 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // rows four apart, which the Q/K row stride (4 banks per row) spreads over all banks; with
     // consecutive rows the 64-byte pieces of eight rows would overlap four deep.
     const int tr_row4 = 16 * g + 4 * (s16 >> 2);
-    const int tr_off_k = tr_row4 * RSQ + 32 * max(st_tile, 0) + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);
+    const int tr_off_k = tr_row4 * RSQ + 32 * tile0 + 16 * half + 8 * (s16 & 1) + 4 * ((s16 >> 1) & 1);  // + 32 u
     const int tr_off_vs = tr_row4 * RSVS + 16 * half + 4 * (s16 & 3);
     const int st_rd_off = ln * RST + 8 * g;  // + 16 s
 
-    // ---- iteration t of the pipeline (t = 0 .. t_end), one body per role.  Each body is
-    // straight-line code that first issues every LDS read the iteration needs and then runs its
-    // MFMAs back to back, so that the reads of one product are in flight under the MFMAs of the
-    // other; the role and edge conditions are resolved outside (tags and peeled iterations).
+    // ---- iteration t, one body per role.  Each body is straight-line code that first issues every
+    // LDS read the iteration needs and then runs its MFMAs back to back; operands that two products
+    // share are read once and stay in registers (the Q rows of a row block serve its score tiles and
+    // its S^T Q^T product; the Gam V fragments serve both state tiles of a state wave), and the
+    // masked scores go from the accumulators straight into the next product as its B operand.
 
-    // Score and state waves, chunk t: G1 (score tile w -> pfrag) and G4 (state tile st_tile).
-    auto score_state = [&](int t, auto do_g1, auto do_g4) {
-        constexpr bool kG1 = decltype(do_g1)::value, kG4 = decltype(do_g4)::value;
+    // State waves, chunk t: S = gamma^L S + K^T (Gam V) for the tiles this wave owns (G4).
+    auto state_tiles = [&](int t) {
         const int qb = t & 1;
         const int shift = (t == n - 1) ? last_shift : 0;
-        u32x4 kf[D / 16], qf[D / 16], ak[4], bv[4];
-        if (kG1) {
-            const int jt = (w == 1) ? 1 : 0, it = (w == 0) ? 0 : 1;  // tiles (0,0), (1,1), (0,1)
-            const uint16_t* ka = &sm.k[qb][row_off + 32 * jt * RSQ];
-            const uint16_t* qa = &sm.q[qb][row_off + 32 * it * RSQ];
+        u32x4 ak[TPW][4], bv[4];
+        const uint16_t* k_tr = &sm.k[qb][tr_off_k];
+        const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) { kf[s] = frag16(ka + 16 * s); qf[s] = frag16(qa + 16 * s); }
+        for (int f = 0; f < 4; ++f) {
+            bv[f] = frag_tr(vs_tr + f * RSVS, 32 * RSVS);
+#pragma unroll
+            for (int u = 0; u < TPW; ++u) ak[u][f] = frag_tr(k_tr + 32 * u + f * RSQ, 32 * RSQ);
         }
-        if (kG4) {
-            const uint16_t* k_tr = &sm.k[qb][tr_off_k];
-            const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
+        const float gl = shift ? sm.pw[kChunk - shift] : gl_full;
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                ak[f] = frag_tr(k_tr + f * RSQ, 32 * RSQ);
-                bv[f] = frag_tr(vs_tr + f * RSVS, 32 * RSVS);
-            }
+        for (int u = 0; u < TPW; ++u) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[u][r] *= gl;
+#pragma unroll
+            for (int f = 0; f < 4; ++f) S[u] = mfma32(ak[u][f], bv[f], S[u]);
         }
-        f32x16 acc = zero16();
-        if (kG1) {
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) acc = mfma32(kf[s], qf[s], acc);
-        }
-        if (kG4) {
-            // S = gamma^L S + K^T (Gam V) for the tile this wave owns
-            const float gl = shift ? sm.pw[kChunk - shift] : gl_full;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] *= gl;
-#pragma unroll
-            for (int f = 0; f < 4; ++f) S = mfma32(ak[f], bv[f], S);
-        }
-        if (kG1) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] *= wgt[r];
-            sm.pfrag[qb][w][0][l] = pack_half<E>(acc, 0);
-            sm.pfrag[qb][w][1][l] = pack_half<E>(acc, 1);
-        }
-        if (kG4 && kOut) publish_state((t + 1) & 1);  // S^T(t+1) for the G3 waves
+        if (kOut) publish_state((t + 1) & 1);  // S^T(t+1) for the row waves
     };
 
-    // Output waves, row block it_own.  kG2: finish chunk t-1 (O^T += V^T P^T over the score tiles of
-    // the row block) and hand it to the store wave; kG3: start chunk t (O^T = S^T Q^T, rows scaled
-    // by gamma^(i+1)).
-    f32x16 o = zero16();  // the row block of the chunk in progress
-    auto output = [&](int t, auto do_g2, auto do_g3, auto do_g4) {
-        constexpr bool kG2 = decltype(do_g2)::value, kG3 = decltype(do_g3)::value, kG4 = decltype(do_g4)::value;
+    // Row waves, chunk t, row block it_own (compile-time kLower = it_own == 1):
+    //   G1  P^T tiles = K rows x Q rows, decay mask: the diagonal tile (it, it) and, for the lower
+    //       row block, the tile (0, 1) under the diagonal
+    //   G3  O^T = S^T Q^T, rows scaled by gamma^(i+1)
+    //   G2  O^T += V^T P^T over the keys of the tiles, then the tile goes to LDS for the store wave
+    auto row_block = [&](int t, auto lower) {
+        constexpr bool kLower = decltype(lower)::value;
+        constexpr int IT = kLower ? 1 : 0;
         const int qb = t & 1;
-        u32x4 sf[D / 16], qf[D / 16], vt[4], pf[4], ak[4], bv[4];
-        if (kG3) {
-            const uint16_t* st_rd = &sm.st[qb][st_rd_off];
-            const uint16_t* qa = &sm.q[qb][row_off + 32 * it_own * RSQ];
+        const int shift = (t == n - 1) ? last_shift : 0;
+        u32x4 qf[D / 16], kd[D / 16], ko[D / 16], sf[D / 16], vt[kLower ? 4 : 2];
+        const uint16_t* qa = &sm.q[qb][row_off + 32 * IT * RSQ];
+        const uint16_t* ka = &sm.k[qb][row_off];
+        const uint16_t* st_rd = &sm.st[qb][st_rd_off];
+        const uint16_t* v_tr = &sm.v[t % 3][tr_off_v];
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) { sf[s] = frag16(st_rd + 16 * s); qf[s] = frag16(qa + 16 * s); }
+        for (int s = 0; s < D / 16; ++s) {
+            if (kLower) ko[s] = frag16(ka + 16 * s);                 // K rows 0..31
+            qf[s] = frag16(qa + 16 * s);
         }
-        if (kG2) {
-            const int pb = (t - 1) & 1;
-            const uint16_t* v_tr = &sm.v[(t - 1) % 3][tr_off_v];
-            if (it_own == 0) {
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) { vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV); pf[hh] = sm.pfrag[pb][0][hh][l]; }
-            } else {
+        for (int s = 0; s < D / 16; ++s) kd[s] = frag16(ka + 32 * IT * RSQ + 16 * s);   // K rows of the diagonal tile
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV);
-                    pf[hh] = sm.pfrag[pb][2][hh][l];
-                    vt[2 + hh] = frag_tr(v_tr + 16 * (2 + hh) * RSV, 8 * RSV);
-                    pf[2 + hh] = sm.pfrag[pb][1][hh][l];
-                }
-            }
+        for (int s = 0; s < D / 16; ++s) sf[s] = frag16(st_rd + 16 * s);
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) o = mfma32(vt[hh], pf[hh], o);
-            if (it_own != 0) {
+        for (int hh = 0; hh < (kLower ? 4 : 2); ++hh) vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV);
+
+        f32x16 po = zero16(), pd = zero16(), o = zero16();
+        if (kLower) {
 #pragma unroll
-                for (int hh = 2; hh < 4; ++hh) o = mfma32(vt[hh], pf[hh], o);
-            }
+            for (int s = 0; s < D / 16; ++s) po = mfma32(ko[s], qf[s], po);
         }
-        if (kG4) {
-            const uint16_t* k_tr = &sm.k[qb][tr_off_k];
-            const uint16_t* vs_tr = &sm.vs[t % 3][tr_off_vs];
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                ak[f] = frag_tr(k_tr + f * RSQ, 32 * RSQ);
-                bv[f] = frag_tr(vs_tr + f * RSVS, 32 * RSVS);
-            }
+        for (int s = 0; s < D / 16; ++s) pd = mfma32(kd[s], qf[s], pd);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) o = mfma32(sf[s], qf[s], o);
+        const float lam = shift ? sm.pw[max(32 * IT + ln + 1 - shift, 0)] : lam_full;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[r] *= lam;
+        if (kLower) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) po[r] *= wgt_o[r];
+            o = mfma32(vt[0], pack_half<E>(po, 0), o);
+            o = mfma32(vt[1], pack_half<E>(po, 1), o);
         }
-        f32x16 o_next = zero16();
-        if (kG3) {
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) o_next = mfma32(sf[s], qf[s], o_next);
-        }
-        if (kG4) {
-            const int shift4 = (t == n - 1) ? last_shift : 0;
-            const float gl = shift4 ? sm.pw[kChunk - shift4] : gl_full;
+        for (int r = 0; r < 16; ++r) pd[r] *= wgt_d[r];
+        o = mfma32(vt[kLower ? 2 : 0], pack_half<E>(pd, 0), o);
+        o = mfma32(vt[kLower ? 3 : 1], pack_half<E>(pd, 1), o);
+        // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
+        float* ot = &sm.obuf[qb][IT][ln * 36 + 4 * g];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] *= gl;
-#pragma unroll
-            for (int f = 0; f < 4; ++f) S = mfma32(ak[f], bv[f], S);
-            publish_state((t + 1) & 1);
-        }
-        if (kG2) {
-            // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
-            float* ot = &sm.obuf[qb][it_own][ln * 36 + 4 * g];
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
-                *reinterpret_cast<f32x4*>(ot + 8 * qd) = val;
-            }
-        }
-        if (kG3) {
-            const int shift = (t == n - 1) ? last_shift : 0;
-            const float lam = shift ? sm.pw[max(32 * it_own + ln + 1 - shift, 0)] : lam_full;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[r] = o_next[r] * lam;
+        for (int qd = 0; qd < 4; ++qd) {
+            f32x4 val = {o[4 * qd], o[4 * qd + 1], o[4 * qd + 2], o[4 * qd + 3]};
+            *reinterpret_cast<f32x4*>(ot + 8 * qd) = val;
         }
     };
 
-    // Store wave: chunk t-2, finished in iteration t-1: whole row pieces per lane group.
-    // Nontemporal: the output is written once and must not displace Q and K, which the sibling
-    // slices re-read, from L2.
+    // Store waves: row block rb = w - 4 of chunk t-1, finished in iteration t-1: whole row pieces
+    // per lane group.  Nontemporal: the output is written once and must not displace Q and K, which
+    // the sibling slices re-read, from L2.
     auto store_chunk = [&](int t) {
-        const int c = t - 2;
+        const int c = t - 1, rb = w - 4;
         const int cshift = (c == n - 1) ? last_shift : 0;
         // offset of the chunk's first token (tile row cshift); rows are counted from there
         const size_t tile_off = (size_t)(tok_begin + c * kChunk) * DV + c0;
         // All LDS reads of the tile are issued before the first store (a read placed under its row's
-        // condition would make every store wait for its own read: eight LDS round trips in a row);
+        // condition would make every store wait for its own read: LDS round trips in a row);
         // a full chunk, the common case, stores without any per-row condition.
         if (!kOut16) {
             // 128-byte row pieces: lane -> (row l/8 of eight rows, 16 bytes l%8)
             float* oc = og + tile_off + 4 * (l & 7);
-            const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 3) * 36 + 4 * (l & 7)];
-            f32x4 val[8];
+            const float* ot = &sm.obuf[c & 1][rb][(l >> 3) * 36 + 4 * (l & 7)];
+            f32x4 val[4];
 #pragma unroll
-            for (int m = 0; m < 8; ++m) val[m] = *reinterpret_cast<const f32x4*>(ot + (m >> 2) * (32 * 36) + (8 * (m & 3)) * 36);
+            for (int m = 0; m < 4; ++m) val[m] = *reinterpret_cast<const f32x4*>(ot + (8 * m) * 36);
             if (cshift == 0) {
 #pragma unroll
-                for (int m = 0; m < 8; ++m)   // row 8 m + l/8 of the 64-row chunk tile; row block m / 4
-                    __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(oc + (size_t)(8 * m + (l >> 3)) * DV));
+                for (int m = 0; m < 4; ++m)   // row 32 rb + 8 m + l/8 of the 64-row chunk tile
+                    __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(oc + (size_t)(32 * rb + 8 * m + (l >> 3)) * DV));
             } else {
 #pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const int row = 8 * m + (l >> 3);
+                for (int m = 0; m < 4; ++m) {
+                    const int row = 32 * rb + 8 * m + (l >> 3);
                     if (row >= cshift) __builtin_nontemporal_store(val[m], reinterpret_cast<f32x4*>(oc + (size_t)(row - cshift) * DV));
                 }
             }
         } else {
             // 64-byte row pieces: lane -> (row l/4 of sixteen rows, eight columns l%4)
             uint16_t* oc = og16 + tile_off + 8 * (l & 3);
-            const float* ot = &sm.obuf[(t - 1) & 1][0][(l >> 2) * 36 + 8 * (l & 3)];
-            u32x4 val[4];
+            const float* ot = &sm.obuf[c & 1][rb][(l >> 2) * 36 + 8 * (l & 3)];
+            u32x4 val[2];
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const float* src = ot + (m >> 1) * (32 * 36) + (16 * (m & 1)) * 36;
+            for (int m = 0; m < 2; ++m) {
+                const float* src = ot + (16 * m) * 36;
                 const f32x4 a = *reinterpret_cast<const f32x4*>(src);
                 const f32x4 b = *reinterpret_cast<const f32x4*>(src + 4);
                 const u32x4 v8 = {E::pack2(a[0], a[1]), E::pack2(a[2], a[3]), E::pack2(b[0], b[1]), E::pack2(b[2], b[3])};
@@ -487,12 +460,12 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             }
             if (cshift == 0) {
 #pragma unroll
-                for (int m = 0; m < 4; ++m)   // row 16 m + l/4; row block m / 2
-                    __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(oc + (size_t)(16 * m + (l >> 2)) * DV));
+                for (int m = 0; m < 2; ++m)   // row 32 rb + 16 m + l/4
+                    __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(oc + (size_t)(32 * rb + 16 * m + (l >> 2)) * DV));
             } else {
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const int row = 16 * m + (l >> 2);
+                for (int m = 0; m < 2; ++m) {
+                    const int row = 32 * rb + 16 * m + (l >> 2);
                     if (row >= cshift) __builtin_nontemporal_store(val[m], reinterpret_cast<u32x4*>(oc + (size_t)(row - cshift) * DV));
                 }
             }
@@ -502,7 +475,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // The loaders and the compute waves run separate loops (so that the register stages are live
     // in the loaders only) that execute the same number of workgroup barriers: one after the
     // prologue and one per iteration t = 0 .. t_end.
-    const int t_end = kOut ? n + 1 : n - 1;  // the walk needs two more iterations to finish and store the last chunk
+    const int t_end = kOut ? n : n - 1;  // the walk needs one more iteration to store the last chunk
     if (loader) {
         // prologue: chunks 0 .. NS-1 in flight, chunk 0 into its buffers, its stage refilled with chunk NS
         Stage stg[NS];
@@ -538,38 +511,23 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         const std::false_type no;
         __syncthreads();
         // every branch below executes one barrier per iteration t = 0 .. t_end
-        if (score_wave) {
-            for (int t = 0; t <= t_end; ++t) {
-                if (t < n) {
-                    if (state_wave) score_state(t, yes, yes);
-                    else score_state(t, yes, no);
-                }
-                __syncthreads();  // chunk t+1 tiles, P(t), S^T(t+1) visible; everything read in this iteration is free
-            }
-        } else if (out_wave) {
-            if (state_wave) {
-                output(0, no, yes, yes);
-                __syncthreads();
-                for (int t = 1; t < n; ++t) {
-                    output(t, yes, yes, yes);
-                    __syncthreads();
+        if (row_wave) {
+            if (it_own == 0) {
+                for (int t = 0; t <= t_end; ++t) {
+                    if (t < n) row_block(t, no);
+                    __syncthreads();  // chunk t+1 tiles, S^T(t+1), O(t) visible; everything read in this iteration is free
                 }
             } else {
-                output(0, no, yes, no);
-                __syncthreads();
-                for (int t = 1; t < n; ++t) {
-                    output(t, yes, yes, no);
+                for (int t = 0; t <= t_end; ++t) {
+                    if (t < n) row_block(t, yes);
                     __syncthreads();
                 }
             }
-            output(n, yes, no, no);
-            __syncthreads();
-            __syncthreads();  // iteration n + 1: the store wave's last chunk
         } else {
-            // wave 5 (the stores of the walk), and in the pre-pass every wave that owns a state tile
+            // the state waves, the store waves of the walk, and waves with nothing to do in this launch
             for (int t = 0; t <= t_end; ++t) {
-                if (state_wave && t < n) score_state(t, no, yes);
-                if (store_wave && t >= 2) store_chunk(t);
+                if (state_wave && t < n) state_tiles(t);
+                if (store_wave && t >= 1) store_chunk(t);
                 __syncthreads();
             }
         }
@@ -584,7 +542,9 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     }
     if (dst && state_wave) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dst[dk_of(r) * DV + c0 + ln] = S[r];
+        for (int u = 0; u < TPW; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[dk_of(u, r) * DV + c0 + ln] = S[u][r];
     }
 }
 

@@ -368,45 +368,88 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         constexpr int IT = kLower ? 1 : 0;
         const int qb = t & 1;
         const int shift = (t == n - 1) ? last_shift : 0;
-        u32x4 qf[D / 16], kd[D / 16], ko[D / 16], sf[D / 16], vt[kLower ? 4 : 2];
+        u32x4 qf[D / 16], kd[D / 16], ko[D / 16], sf[D / 16], vt[4];
         const uint16_t* qa = &sm.q[qb][row_off + 32 * IT * RSQ];
         const uint16_t* ka = &sm.k[qb][row_off];
         const uint16_t* st_rd = &sm.st[qb][st_rd_off];
         const uint16_t* v_tr = &sm.v[t % 3][tr_off_v];
+        // The operands are read in items of four LDS instructions, in the order in which the MFMAs
+        // take them, and each item is issued kAhead items before it is used: the reads of the next
+        // items are then in flight under the MFMAs of this one (the counter of outstanding LDS
+        // operations holds 15, so everything cannot be issued up front, and reading an item just
+        // before its MFMAs puts one LDS round trip in front of every pair of them).
+        //   lower row block: NP items {K rows 0..31, Q} for the tile under the diagonal, NQ items of
+        //   K rows 32..63 for the diagonal tile, NQ items of S^T, two items of V^T
+        //   upper row block: NP items {K rows 0..31, Q} for the diagonal tile, NQ items of S^T, one of V^T
+        constexpr int NP = D / 32, NQ = D / 64, kAhead = 3;
+        constexpr int NM = kLower ? NP + 2 * NQ : NP + NQ;   // items with MFMAs of their own
+        constexpr int NR = NM + (kLower ? 2 : 1);            // all items
+        auto issue = [&](int i) {
+            if (i >= NR) return;
+            if (i < NP) {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            if (kLower) ko[s] = frag16(ka + 16 * s);                 // K rows 0..31
-            qf[s] = frag16(qa + 16 * s);
+                for (int s = 2 * i; s < 2 * i + 2; ++s) {
+                    if (kLower) ko[s] = frag16(ka + 16 * s);
+                    else kd[s] = frag16(ka + 16 * s);
+                    qf[s] = frag16(qa + 16 * s);
+                }
+            } else if (kLower && i < NP + NQ) {
+#pragma unroll
+                for (int s = 4 * (i - NP); s < 4 * (i - NP) + 4; ++s) kd[s] = frag16(ka + 32 * RSQ + 16 * s);
+            } else if (i < NM) {
+#pragma unroll
+                for (int s = 4 * (i - (NM - NQ)); s < 4 * (i - (NM - NQ)) + 4; ++s) sf[s] = frag16(st_rd + 16 * s);
+            } else {
+#pragma unroll
+                for (int hh = 2 * (i - NM); hh < 2 * (i - NM) + 2; ++hh) vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV);
+            }
+        };
+        f32x16 po = zero16(), pd = zero16(), os = zero16(), o = zero16();
+        u32x4 pfo[2], pfd[2];
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i) issue(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            if (i < NP) {
+#pragma unroll
+                for (int s = 2 * i; s < 2 * i + 2; ++s) {
+                    if (kLower) po = mfma32(ko[s], qf[s], po);
+                    else pd = mfma32(kd[s], qf[s], pd);
+                }
+            } else if (kLower && i < NP + NQ) {
+#pragma unroll
+                for (int s = 4 * (i - NP); s < 4 * (i - NP) + 4; ++s) pd = mfma32(kd[s], qf[s], pd);
+            } else {
+#pragma unroll
+                for (int s = 4 * (i - (NM - NQ)); s < 4 * (i - (NM - NQ)) + 4; ++s) os = mfma32(sf[s], qf[s], os);
+            }
+            issue(i + kAhead);
+            // mask and pack a score tile once the MFMAs of the next product have been issued behind it
+            if (kLower && i == NP + NQ - 1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) po[r] *= wgt_o[r];
+                pfo[0] = pack_half<E>(po, 0);
+                pfo[1] = pack_half<E>(po, 1);
+            }
+            if (i == NM - 1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) pd[r] *= wgt_d[r];
+                pfd[0] = pack_half<E>(pd, 0);
+                pfd[1] = pack_half<E>(pd, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) kd[s] = frag16(ka + 32 * IT * RSQ + 16 * s);   // K rows of the diagonal tile
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) sf[s] = frag16(st_rd + 16 * s);
-#pragma unroll
-        for (int hh = 0; hh < (kLower ? 4 : 2); ++hh) vt[hh] = frag_tr(v_tr + 16 * hh * RSV, 8 * RSV);
-
-        f32x16 po = zero16(), pd = zero16(), o = zero16();
+        // V^T P^T into an accumulator of its own, so that it does not wait for the scaling of S^T Q^T
         if (kLower) {
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) po = mfma32(ko[s], qf[s], po);
+            o = mfma32(vt[0], pfo[0], o);
+            o = mfma32(vt[1], pfo[1], o);
         }
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) pd = mfma32(kd[s], qf[s], pd);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) o = mfma32(sf[s], qf[s], o);
+        o = mfma32(vt[kLower ? 2 : 0], pfd[0], o);
+        o = mfma32(vt[kLower ? 3 : 1], pfd[1], o);
         const float lam = shift ? sm.pw[max(32 * IT + ln + 1 - shift, 0)] : lam_full;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[r] *= lam;
-        if (kLower) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) po[r] *= wgt_o[r];
-            o = mfma32(vt[0], pack_half<E>(po, 0), o);
-            o = mfma32(vt[1], pack_half<E>(po, 1), o);
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) pd[r] *= wgt_d[r];
-        o = mfma32(vt[kLower ? 2 : 0], pack_half<E>(pd, 0), o);
-        o = mfma32(vt[kLower ? 3 : 1], pack_half<E>(pd, 1), o);
+        for (int r = 0; r < 16; ++r) o[r] = __builtin_fmaf(os[r], lam, o[r]);
         // hand the tile to the store wave: lane = token 32 it + ln, registers 4q..4q+3 = columns 8q + 4g + (0..3)
         float* ot = &sm.obuf[qb][IT][ln * 36 + 4 * g];
 #pragma unroll

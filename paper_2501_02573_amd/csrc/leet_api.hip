@@ -113,13 +113,13 @@ struct CostModel {
     double wide_crowded;                        // transfer-time factor with more wide workgroups than CUs
     int wide_slots;                             // wide workgroups resident on the device
 };
-constexpr CostModel kCost128 = {2.726, 1.020, 0.896, 0.361, 8.0e6, 6.746e6, 8.0e6, 5.816e6,
-                                3.62, 10.07, 0.353, 2.287, 2.0, 1.260, 512};
-constexpr CostModel kCost64 = {1.951, 0.574, 0.632, 0.277, 7.315e6, 5.988e6, 8.0e6, 5.662e6,
-                               3.53, 9.65, 0.345, 2.885, 2.617, 1.126, 1024};
+constexpr CostModel kCost128 = {2.718, 0.935, 0.776, 0.391, 8.0e6, 6.734e6, 7.699e6, 5.352e6,
+                                3.62, 10.26, 0.341, 2.270, 2.0, 1.256, 512};
+constexpr CostModel kCost64 = {1.839, 0.516, 0.546, 0.287, 7.540e6, 6.094e6, 8.0e6, 5.553e6,
+                               3.01, 9.10, 0.351, 3.085, 2.567, 1.167, 1024};
 // rank 128, value width 256: one wide workgroup per compute unit (512 threads)
-constexpr CostModel kCost128x256 = {3.402, 1.695, 0.827, 0.412, 8.0e6, 6.681e6, 6.391e6, 4.646e6,
-                                    4.22, 10.35, 0.426, 2.532, 2.0, 1.163, 256};
+constexpr CostModel kCost128x256 = {3.172, 1.643, 0.733, 0.427, 8.0e6, 6.706e6, 6.553e6, 4.692e6,
+                                    4.32, 10.17, 0.426, 2.229, 2.0, 1.158, 256};
 constexpr double kOneKernelFloorUs = 11.0;    // shortest call seen end to end, one and three kernels
 constexpr double kThreeKernelFloorUs = 17.0;
 constexpr int kCoopSlots = 256;               // one column-split workgroup per compute unit
@@ -139,8 +139,8 @@ double predicted_us(bool coop, long BH, int N, int D, int DV, int nseg, int seg_
         const long per_seg = BH * (DV / 32);
         const double bw = m.coop_bw_cached * (1.0 - spill) + m.coop_bw_streamed * spill;
         const long rounds = (per_seg * nseg + kCoopSlots - 1) / kCoopSlots;
-        // the walk's software pipeline runs two iterations beyond the chunks of a segment
-        const double walk = smooth_max(rounds * (seg_chunks + 2) * m.coop_chunk_us, (in_bytes + out_bytes) / bw, m.coop_p);
+        // the walk's software pipeline runs one iteration beyond the chunks of a segment
+        const double walk = smooth_max(rounds * (seg_chunks + 1) * m.coop_chunk_us, (in_bytes + out_bytes) / bw, m.coop_p);
         if (nseg == 1) return fmax(kOneKernelFloorUs, m.one_kernel_us + walk);
         const long pre_rounds = (per_seg * (nseg - 1) + kCoopSlots - 1) / kCoopSlots;
         const double pre = smooth_max(pre_rounds * seg_chunks * m.coop_pre_chunk_us, pre_bytes / bw, m.coop_p);
@@ -161,7 +161,8 @@ double predicted_us(bool coop, long BH, int N, int D, int DV, int nseg, int seg_
 // D: width of q and k rows (rank); DV: width of v and out rows
 //
 // 16-bit inputs: every eligible (kernel, segment count) pair is priced with the cost model
-// and the cheapest taken (ties go to fewer segments, then to the column-split kernel).  A caller's
+// and the cheapest taken (near-ties go to fewer segments, then to the column-split kernel while its
+// grid fits one round of workgroups, else to the wide kernel).  A caller's
 // segment count or kernel choice narrows the candidates.  fp32 keeps the rule of
 // about one workgroup per compute unit with a minimum segment length.  The plan depends on the
 // shape, the input type, the segment request and the kernel knob only -- not on the output type or
@@ -204,11 +205,16 @@ bool make_plan(long BH, int N, int D, int DV, int dtype, int segments, int choic
             int nseg, seg_chunks;
             round_segments(want, &nseg, &seg_chunks);
             if (segments == 0 && nseg > 1 && seg_chunks < 2) break;
-            for (int c = 1; c >= 0; --c) {
+            // A later candidate must be 2 % cheaper to replace an earlier one, so the order decides
+            // near-ties: fewer segments first, and at one segment count the column-split kernel first
+            // unless its grid exceeds one round of workgroups (there the model is least sure of it).
+            const bool coop_first = BH * (DV / 32) * nseg <= kCoopSlots;
+            for (int turn = 0; turn < 2; ++turn) {
+                const bool c = (turn == 0) == coop_first;
                 if (c ? !try_coop : !try_wide) continue;
-                const double t = predicted_us(c != 0, BH, N, D, DV, nseg, seg_chunks);
+                const double t = predicted_us(c, BH, N, D, DV, nseg, seg_chunks);
                 if (!have || t < best * 0.98) {
-                    have = true; best = t; best_coop = c != 0; best_nseg = nseg; best_chunks = seg_chunks;
+                    have = true; best = t; best_coop = c; best_nseg = nseg; best_chunks = seg_chunks;
                 }
             }
             if (segments > 0) break;

@@ -169,11 +169,13 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     const int c0 = 32 * slice;
 
     // ---- roles
-    constexpr int TPW = (DT >= 2) ? DT / 2 : 1;                  // state tiles per state wave
+    // state tiles per state wave: the walk has two state waves (2, 3); the pre-pass, in which nothing
+    // else computes, spreads the tiles over waves 0 .. DT-1, one each
+    constexpr int TPW = kOut ? ((DT >= 2) ? DT / 2 : 1) : 1;
     const bool row_wave = kOut && w < 2;                         // scores, G3 and G2 of row block it_own = w
     const int it_own = w & 1;
-    const int tw = w - 2;                                        // state wave number
-    const bool state_wave = (w == 2 || w == 3) && tw * TPW < DT; // G4 for state tiles tw TPW .. tw TPW + TPW - 1
+    const int tw = kOut ? w - 2 : w;                             // state wave number
+    const bool state_wave = tw >= 0 && tw * TPW < DT && (!kOut || w < 4);   // G4 for state tiles tw TPW .. tw TPW + TPW - 1
     const int tile0 = max(tw, 0) * TPW;
     const bool store_wave = kOut && (w == 4 || w == 5);          // writes the finished O tile of row block w - 4 to global memory
     const bool loader = w >= 6;

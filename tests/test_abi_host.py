@@ -165,8 +165,8 @@ def test_kernel_choice_setter_and_plan_query(lib):
 
 
 def test_planner_against_measured_sweep(lib):
-    """The planner's pick is within 15 % of the fastest measured (kernel, segment count) pair on every
-    shape of the tabulated sweep (three shapes of 266 exceed 10 %), and within 1 % on average."""
+    """The planner's pick is within 12 % of the fastest measured (kernel, segment count) pair on every
+    shape of the tabulated sweep (the worst of 262 is 8.3 %), and within 1 % on average (0.24 %)."""
     import json
     from paper_2501_02573_amd import binding as b
     table = json.load(open(os.path.join(ROOT, "profiles", "plan_sweep.json")))
@@ -183,7 +183,7 @@ def test_planner_against_measured_sweep(lib):
         if label not in runs:      # a rounded segment count that the sweep did not time
             continue
         ratio = runs[label] / min(runs.values())
-        assert ratio <= 1.15, (key, label, runs[label], min(runs.values()))
+        assert ratio <= 1.12, (key, label, runs[label], min(runs.values()))
         ratios.append(ratio)
     assert len(ratios) >= 200
     assert sum(ratios) / len(ratios) <= 1.01

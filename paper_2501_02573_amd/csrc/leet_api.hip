@@ -734,6 +734,6 @@ int leet_attn_set_decode_store(int mode) {
 
 int leet_attn_get_decode_store(void) { return g_decode_store.load(std::memory_order_relaxed); }
 
-const char* leet_attn_version(void) { return "0.6.0"; }
+const char* leet_attn_version(void) { return "0.7.0"; }
 
 }  // extern "C"

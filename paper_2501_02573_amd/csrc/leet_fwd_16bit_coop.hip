@@ -193,11 +193,6 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     float* og = static_cast<float*>(p.out) + seq_off_v;                     // fp32 output
     uint16_t* og16 = static_cast<uint16_t*>(p.out) + seq_off_v;             // output in the input type
 
-    {
-        const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
-        for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);
-    }
-
     // ---- state tiles of this wave: S[u][r] = S[dk = 32 (tile0 + u) + pi(m(r, g))][c = c0 + ln]
     auto dk_of = [&](int u, int r) {
         // m = 8(r/4) + 4g + r%4 ; pi swaps the 4- and 8-bits: dk = 16(r/8) + 8g + 4((r/4)&1) + r%4
@@ -269,11 +264,13 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             st.v[m] = *reinterpret_cast<const u32x4*>(vc + (unsigned)(max(v_row + VRS * m - shift, 0) * DV + c0 + v_cc * 8));
     };
 
-    __syncthreads();  // tables, S^T(0) visible
-
+    // The table of decay weights gamma^n and everything derived from it are filled in behind the
+    // first workgroup barrier, which each role executes in its own branch below: the loaders put
+    // the first chunks' loads in flight before they wait there, so that the arrival of gamma from
+    // memory, the table and the first tile's way from memory overlap.
     float v_scale[VPL];  // gamma^(63-j) for this loader thread's V rows
 #pragma unroll
-    for (int m = 0; m < VPL; ++m) v_scale[m] = sm.pw[kChunk - 1 - min(max(v_row, 0) + VRS * m, kChunk - 1)];
+    for (int m = 0; m < VPL; ++m) v_scale[m] = 0.0f;
     auto store_tiles = [&](Stage& st, int c) {
         const int shift = (c == n - 1) ? last_shift : 0;
         const int qb = c & 1, vb = c % 3;
@@ -309,16 +306,20 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // decay weights of the two kinds of score tile, i - j = 32 (it - jt) + ln - jr: the diagonal
     // tiles (jt = it) and the one below the diagonal (jt = 0, it = 1; row wave 1 only)
     f32x16 wgt_d = zero16(), wgt_o = zero16();
-    if (row_wave) {
+    float lam_full = 0.0f;   // gamma^(i+1) in a full chunk
+    float gl_full = 0.0f;    // gamma^64
+    auto read_tables = [&]() {   // after the first barrier
+        if (row_wave) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int d = ln - (8 * (r >> 2) + 4 * g + (r & 3));
-            wgt_d[r] = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
-            wgt_o[r] = sm.pw[32 + d];
+            for (int r = 0; r < 16; ++r) {
+                int d = ln - (8 * (r >> 2) + 4 * g + (r & 3));
+                wgt_d[r] = (d >= 0) ? sm.pw[max(d, 0)] : 0.0f;
+                wgt_o[r] = sm.pw[32 + d];
+            }
         }
-    }
-    const float lam_full = sm.pw[min(32 * it_own + ln + 1, kChunk)];  // gamma^(i+1) in a full chunk
-    const float gl_full = sm.pw[kChunk];                               // gamma^64
+        lam_full = sm.pw[min(32 * it_own + ln + 1, kChunk)];
+        gl_full = sm.pw[kChunk];
+    };
     const int row_off = ln * RSQ + 8 * g;  // 16-byte row fragments of Q, K: + 32 tile RSQ + 16 s
     // transposing reads: lane supplies row 4g + s16/4 (+ 16 f, + 8 for the second half) and four columns
     const int tr_off_v = (4 * g + (s16 >> 2)) * RSV + 16 * half + 4 * (s16 & 3);
@@ -526,6 +527,9 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         Stage stg[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) prefetch(stg[s], s);
+        __syncthreads();  // tables, S^T(0) visible
+#pragma unroll
+        for (int m = 0; m < VPL; ++m) v_scale[m] = sm.pw[kChunk - 1 - min(max(v_row, 0) + VRS * m, kChunk - 1)];
         store_tiles(stg[0], 0);
         prefetch(stg[0], NS);
         __syncthreads();
@@ -554,6 +558,12 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     } else {
         const std::true_type yes;
         const std::false_type no;
+        {
+            const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
+            for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);   // threads 0 .. 64: waves 0 and 1
+        }
+        __syncthreads();  // tables, S^T(0) visible
+        read_tables();
         __syncthreads();
         // every branch below executes one barrier per iteration t = 0 .. t_end
         if (row_wave) {

@@ -25,7 +25,9 @@
 //                G2  O^T += V^T P^T (V through transposing LDS reads, P^T straight from the G1
 //                    accumulators: a P^T accumulator, lane = query, registers = keys, is a B operand
 //                    as it is); the finished tile goes to LDS for the store wave.
-//                The Q rows are read once for all three products.
+//                The Q rows of a row block are used by this wave alone, so they never enter LDS:
+//                the wave loads its own operand fragments from global memory into registers, one
+//                chunk ahead, and uses them for all three products.
 //   waves 2, 3   G4  S[dk tile][c] = gamma^L S + K^T (Gam V) for two of the four 32-row state tiles
 //                    each (one of two at d = 64), A = K through transposing reads, B = the Gam-scaled
 //                    V copy, read once for both tiles; the owner keeps its fp32 tiles in accumulators
@@ -34,7 +36,7 @@
 //   waves 4, 5   store the finished O tile of row block w - 4 in whole row pieces (and nothing else:
 //                    their stores queue behind the loaders' loads in the compute unit's one
 //                    vector-memory pipeline)
-//   waves 6, 7   loaders: all global loads of the workgroup and the LDS writes of the tiles
+//   waves 6, 7   loaders: the global loads of K and V and the LDS writes of their tiles
 //
 // A compute unit accepts only so many outstanding vector-memory requests, and a wave that
 // issues one more stalls at that instruction until there is room; a wave that both loads and
@@ -43,7 +45,7 @@
 // the compute waves run, and the only thing that ties the two together is one workgroup
 // barrier per chunk.  The chunk is software-pipelined over that barrier: in iteration t the row
 // waves produce O(t), the state waves S(t+1), the store waves write chunk t-1 to memory, and
-// the loaders write chunk t+1 to LDS and issue the loads of chunk t+3.  Q and K tiles, S^T and the
+// the loaders write chunk t+1 to LDS and issue the loads of chunk t+3.  The K tile, S^T and the
 // output tiles are double-buffered in LDS, the V slice and its scaled copy triple-buffered.
 //
 // MFMA conventions (32x32x16): an A (B) operand holds, in lane l, row (column) l%32 and the
@@ -73,7 +75,6 @@ struct CoopSmem {
     static constexpr int RSV = 32;
     static constexpr int RSVS = 40;
     static constexpr int RST = D + 8;   // S^T[c][dk]
-    uint16_t q[2][kChunk * RSQ];
     uint16_t k[2][kChunk * RSQ];
     uint16_t v[3][kChunk * RSV];
     uint16_t vs[3][kChunk * RSVS];      // Gam V: row j scaled by gamma^(63-j)
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     // stage measured no faster: the loaders are bound by the rate at which one compute unit
     // can pull data through its vector memory path, not by latency.)
     struct Stage {
-        u32x4 q[QPL], k[QPL], v[VPL];
+        u32x4 k[QPL], v[VPL];
     };
     // Loads are unconditional (rows above a ragged chunk's first token re-read that token and
     // are zeroed when the stage is written to LDS; chunks past the end re-read the last one), so
@@ -256,7 +257,6 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         for (int m = 0; m < QPL; ++m) {
             const int row = max(qk_row + m * RPL - shift, 0);
             const unsigned off = (unsigned)(row * D + qk_cc * 8);
-            if (kOut) st.q[m] = *reinterpret_cast<const u32x4*>(qc + off);
             st.k[m] = *reinterpret_cast<const u32x4*>(kc + off);
         }
 #pragma unroll
@@ -278,17 +278,13 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int m = 0; m < QPL; ++m)
-                if (qk_row + m * RPL < shift) {
-                    if (kOut) st.q[m] = z;
-                    st.k[m] = z;
-                }
+                if (qk_row + m * RPL < shift) st.k[m] = z;
 #pragma unroll
             for (int m = 0; m < VPL; ++m)
                 if (v_row + VRS * m < shift) st.v[m] = z;
         }
 #pragma unroll
         for (int m = 0; m < QPL; ++m) {
-            if (kOut) *reinterpret_cast<u32x4*>(&sm.q[qb][qk_loff + m * RPL * RSQ]) = st.q[m];
             *reinterpret_cast<u32x4*>(&sm.k[qb][qk_loff + m * RPL * RSQ]) = st.k[m];
         }
 #pragma unroll
@@ -366,24 +362,39 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     //       row block, the tile (0, 1) under the diagonal
     //   G3  O^T = S^T Q^T, rows scaled by gamma^(i+1)
     //   G2  O^T += V^T P^T over the keys of the tiles, then the tile goes to LDS for the store wave
-    auto row_block = [&](int t, auto lower) {
+    // Q rows of a row block are used by that block's row wave only, so they do not pass through LDS:
+    // the wave loads its own B-operand fragments (lane = query row, 16 bytes at column 16 s + 8 g)
+    // straight from global memory into registers, one chunk ahead.
+    auto load_q = [&](u32x4 (&qn)[D / 16], int c, int it) {
+        c = min(c, n - 1);
+        const int shift = (c == n - 1) ? last_shift : 0;
+        const uint16_t* qrow = qg + ((size_t)(tok_begin + c * kChunk) + max(32 * it + ln - shift, 0)) * D + 8 * g;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) qn[s] = *reinterpret_cast<const u32x4*>(qrow + 16 * s);
+    };
+    auto row_block = [&](int t, auto lower, u32x4 (&qf)[D / 16], u32x4 (&qn)[D / 16]) {
         constexpr bool kLower = decltype(lower)::value;
         constexpr int IT = kLower ? 1 : 0;
         const int qb = t & 1;
         const int shift = (t == n - 1) ? last_shift : 0;
-        u32x4 qf[D / 16], kd[D / 16], ko[D / 16], sf[D / 16], vt[4];
-        const uint16_t* qa = &sm.q[qb][row_off + 32 * IT * RSQ];
+        load_q(qn, t + 1, IT);   // the next chunk's fragments
+        if (shift && 32 * IT + ln < shift) {   // ragged last chunk: rows above its first token are zero
+            const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) qf[s] = z;
+        }
+        u32x4 kd[D / 16], ko[D / 16], sf[D / 16], vt[4];
         const uint16_t* ka = &sm.k[qb][row_off];
         const uint16_t* st_rd = &sm.st[qb][st_rd_off];
         const uint16_t* v_tr = &sm.v[t % 3][tr_off_v];
-        // The operands are read in items of four LDS instructions, in the order in which the MFMAs
+        // The LDS operands are read in items of two to four LDS instructions, in the order in which the MFMAs
         // take them, and each item is issued kAhead items before it is used: the reads of the next
         // items are then in flight under the MFMAs of this one (the counter of outstanding LDS
         // operations holds 15, so everything cannot be issued up front, and reading an item just
         // before its MFMAs puts one LDS round trip in front of every pair of them).
-        //   lower row block: NP items {K rows 0..31, Q} for the tile under the diagonal, NQ items of
+        //   lower row block: NP items of K rows 0..31 for the tile under the diagonal, NQ items of
         //   K rows 32..63 for the diagonal tile, NQ items of S^T, two items of V^T
-        //   upper row block: NP items {K rows 0..31, Q} for the diagonal tile, NQ items of S^T, one of V^T
+        //   upper row block: NP items of K rows 0..31 for the diagonal tile, NQ items of S^T, one of V^T
         constexpr int NP = D / 32, NQ = D / 64, kAhead = 3;
         constexpr int NM = kLower ? NP + 2 * NQ : NP + NQ;   // items with MFMAs of their own
         constexpr int NR = NM + (kLower ? 2 : 1);            // all items
@@ -394,7 +405,6 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
                 for (int s = 2 * i; s < 2 * i + 2; ++s) {
                     if (kLower) ko[s] = frag16(ka + 16 * s);
                     else kd[s] = frag16(ka + 16 * s);
-                    qf[s] = frag16(qa + 16 * s);
                 }
             } else if (kLower && i < NP + NQ) {
 #pragma unroll
@@ -558,6 +568,8 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
     } else {
         const std::true_type yes;
         const std::false_type no;
+        u32x4 qa[D / 16], qb2[D / 16];
+        if (row_wave) load_q(qa, 0, it_own);   // in flight before the table's barrier, like the loaders' first loads
         {
             const double gd = p.no_decay ? 1.0 : (double)p.gamma[h];  // 0/1 causal mask: every weight is 1
             for (int i = tid; i <= kChunk; i += NT) sm.pw[i] = (float)pow_int(gd, i);   // threads 0 .. 64: waves 0 and 1
@@ -567,15 +579,25 @@ __global__ __launch_bounds__(kCoopThreads) void fwd_16bit_coop_kernel(FwdParams 
         __syncthreads();
         // every branch below executes one barrier per iteration t = 0 .. t_end
         if (row_wave) {
+            // qa, qb2: the Q fragments of the chunk in progress and of the next one, in turn (qa holds
+            // chunk 0, loaded before the first barrier)
             if (it_own == 0) {
-                for (int t = 0; t <= t_end; ++t) {
-                    if (t < n) row_block(t, no);
+                for (int t = 0; t <= t_end; t += 2) {
+                    if (t < n) row_block(t, no, qa, qb2);
                     __syncthreads();  // chunk t+1 tiles, S^T(t+1), O(t) visible; everything read in this iteration is free
+                    if (t + 1 <= t_end) {
+                        if (t + 1 < n) row_block(t + 1, no, qb2, qa);
+                        __syncthreads();
+                    }
                 }
             } else {
-                for (int t = 0; t <= t_end; ++t) {
-                    if (t < n) row_block(t, yes);
+                for (int t = 0; t <= t_end; t += 2) {
+                    if (t < n) row_block(t, yes, qa, qb2);
                     __syncthreads();
+                    if (t + 1 <= t_end) {
+                        if (t + 1 < n) row_block(t + 1, yes, qb2, qa);
+                        __syncthreads();
+                    }
                 }
             }
         } else {

@@ -199,15 +199,13 @@ def prefill_leg(torch, binding, W, cfg, dev, steps, warmup, segments, use_graph,
     q, k, v, gamma = (t.to(dev) for t in W.make_forward_inputs(cfg))
     out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
 
-    def step():
-        binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=segments)
+    # argument checks and marshalling done once; a step is one call into the C ABI
+    step = binding.PreparedForward(q, k, v, gamma, out, segments=segments)
 
     cond = step
     if second_set:
         q2, k2, v2, out2 = (torch.empty_like(t).copy_(t) for t in (q, k, v, out))
-
-        def cond():
-            binding.leet_attn_forward_ex(q2, k2, v2, gamma, out=out2, segments=segments)
+        cond = binding.PreparedForward(q2, k2, v2, gamma, out2, segments=segments)
 
     ms_eager, ms_events = time_eager(torch, step, steps, warmup, cond)
     stats = time_reps(torch, step, rep_steps, rep_warmup, cond=cond)
@@ -254,20 +252,20 @@ def main():
     out = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     time.sleep(1.0)
-    ms_cold_clock, _ = time_eager(torch, lambda: binding.leet_attn_forward_ex(q, k, v, gamma, out=out, segments=args.segments),
+    ms_cold_clock, _ = time_eager(torch, binding.PreparedForward(q, k, v, gamma, out, segments=args.segments),
                                   args.steps, args.warmup, cond=None)
     # three input sets in rotation: 603 MB of q, k, v, so that no step finds its inputs in the 256 MB
     # last-level cache (the plain loop re-reads the same 201 MB every step)
     sets = [(q, k, v, out)] + [tuple(torch.empty_like(t).copy_(t) for t in (q, k, v, out)) for _ in range(2)]
+    calls = [binding.PreparedForward(a, b, c, gamma, o, segments=args.segments) for a, b, c, o in sets]
     turn = [0]
 
     def rotating_step():
-        a, b, c, o = sets[turn[0] % 3]
         turn[0] += 1
-        binding.leet_attn_forward_ex(a, b, c, gamma, out=o, segments=args.segments)
+        calls[turn[0] % 3]()
 
     cold_stats = time_reps(torch, rotating_step, 60, 120, cond=rotating_step)
-    del sets, q, k, v, out
+    del sets, calls, q, k, v, out
 
     # Duration of the dominant kernel.  With one segment the step is that one kernel, and the HIP
     # events around the timed steps give its average launch-to-launch time in the timed region

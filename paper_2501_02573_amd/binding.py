@@ -505,6 +505,44 @@ def leet_attn_forward_v3(q, k, v, gamma: Optional[torch.Tensor], out: Optional[t
     return out
 
 
+class PreparedForward:
+    """``leet_attn_forward_v3`` with the argument checks and the marshalling done once.
+
+    For a serving loop that calls the library again and again on the same buffers (contents may
+    change, addresses and shapes may not): calling the object makes one ctypes call into
+    ``leet_attn_forward_v3`` on the device's current stream (or on ``stream``, a raw stream handle,
+    if one was given) and nothing else.  The object keeps the tensors alive."""
+
+    def __init__(self, q, k, v, gamma: Optional[torch.Tensor], out: torch.Tensor,
+                 state_in: Optional[torch.Tensor] = None, state_out: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None, segments: int = 0,
+                 kernel: int = LEET_CHOICE_DEFAULT, mask: int = LEET_MASK_DECAY, stream: Optional[int] = None):
+        B, H, N, r, dv = _check_rd(q, k, v, gamma, out, True)
+        _check_states_rd(B, H, r, dv, state_in=state_in, state_out=state_out)
+        ws_bytes = 0
+        if workspace is not None:
+            if workspace.dtype != torch.uint8:
+                raise TypeError("workspace must be a uint8 tensor")
+            ws_bytes = workspace.numel()
+        self._dev = _check_dev(q, k, v, gamma, out, state_in, state_out, workspace)
+        self._keep = (q, k, v, gamma, out, state_in, state_out, workspace)
+        self._args = (_ptr(q), _ptr(k), _ptr(v), _ptr(gamma), _ptr(out), _ptr(state_in), _ptr(state_out),
+                      _ptr(workspace), ws_bytes, int(segments), int(kernel), B, H, N, r, dv,
+                      _dtype_code(q), _dtype_code(out), int(mask))
+        self._stream = None if stream is None else ctypes.c_void_p(stream)
+        self._fn = lib.leet_attn_forward_v3
+        self.out = out
+
+    def __call__(self) -> torch.Tensor:
+        if torch.cuda.current_device() != self._dev.index:
+            raise ValueError("PreparedForward called with another device current")
+        stream = self._stream if self._stream is not None else ctypes.c_void_p(torch.cuda.current_stream(self._dev).cuda_stream)
+        st = self._fn(*self._args, stream)
+        if st != LEET_OK:
+            raise LeetAttnError(st, "leet_attn_forward_v3")
+        return self.out
+
+
 def workspace_bytes_v3(B: int, H: int, N: int, r: int, dv: int, dtype: int, segments: int = 0,
                        kernel: int = LEET_CHOICE_DEFAULT) -> int:
     return int(lib.leet_attn_workspace_bytes_v3(B, H, N, r, dv, dtype, segments, kernel))

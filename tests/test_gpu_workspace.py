@@ -247,3 +247,24 @@ def test_empty_sequence_hands_the_state_on(B, dtype, d):
     torch.cuda.synchronize()
     check(out.cpu().numpy(), ref, dtype, "prompt after an empty piece vs oracle")
     check(s_end.cpu().numpy(), s_ref, dtype, "state after [] + [all] vs oracle")
+
+
+def test_prepared_call_equals_the_plain_call(B):
+    """PreparedForward marshals once and then only calls leet_attn_forward_v3: same bits as the plain
+    binding call, also after the inputs' contents change and with the state handed on."""
+    Bn, H, N, d = 2, 6, 1000, 128
+    q, k, v, gamma = W.make_custom_forward_inputs(Bn, H, N, d, "bf16", seed=91)
+    dq, dk, dv, dg = dev(q, k, v, gamma)
+    out_p = torch.zeros((Bn, H, N, d), dtype=torch.float32, device="cuda")
+    s_p = torch.zeros((Bn, H, d, d), dtype=torch.float32, device="cuda")
+    call = B.PreparedForward(dq, dk, dv, dg, out_p, state_out=s_p, segments=3)
+    for rep in range(2):
+        say(f"  prepared call, round {rep}")
+        assert call() is out_p
+        s_e = torch.empty_like(s_p)
+        out_e = B.leet_attn_forward_ex(dq, dk, dv, dg, state_out=s_e, segments=3)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p, out_e) and torch.equal(s_p, s_e)
+        dq.mul_(0.5)   # same buffers, new contents
+    with pytest.raises(ValueError):
+        B.PreparedForward(dq, dk, dv[:, :, :10].contiguous(), dg, out_p)
